@@ -1,0 +1,131 @@
+/*
+ * rainfusion.h -- C ABI of the MI355X (gfx950) implementation of RainFusion's
+ * per-head sparse 3D attention (arxiv 2505.21036): the ARM head classifier
+ * (Sec. 3.3, Eq. 6, Alg. 1) and the block-sparse attention forward pass that
+ * applies each head's pattern (Sec. 3.1-3.2, Eq. 1-5; Fig. 2a).
+ *
+ * Conventions for every entry point
+ *   - Tensors are DEVICE pointers owned by the caller: bf16, contiguous
+ *     [B, nH, N, D] (batch, head, token, channel).  The library neither frees nor
+ *     keeps them.  D is 64, 96 or 128.
+ *   - Token order (Sec. 3.1): T frames of H*W tokens each, frame-major, row-major
+ *     inside a frame; text_len text tokens follow the video tokens.
+ *     N = T*H*W + text_len.
+ *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and never synchronise it, except that the first call for a new
+ *     (layout, params, block) builds and uploads its block lists synchronously.
+ *   - Return value: RF_OK or a negative rf_status.  Arguments are validated before
+ *     any GPU work, so a bad argument never launches a kernel.
+ *   - `params == NULL` selects the paper's defaults (Sec. 4.1: both bandwidths 1/4,
+ *     checkerboard stride 2) and sampling interval T.
+ */
+#ifndef RAINFUSION_H
+#define RAINFUSION_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Latent video shape (Sec. 3.1) plus the number of appended text tokens. */
+typedef struct {
+    int32_t T, H, W, text_len;
+} rf_layout;
+
+/* Pattern parameters.
+ *   bw_spatial  : Spatial head (Eq. 3) keeps frames f' with |f - f'| <= floor(bw_spatial * T).
+ *   bw_temporal : Temporal head keeps in-frame positions p' with |p - p'| <= floor(bw_temporal * H*W),
+ *                 in every frame.  Both products are formed in double precision.
+ *   tex_stride  : tau of Eq. 4; a key at row y, column x of any frame survives iff (y - x) mod tau == 0.
+ *   sample_interval : omega of Sec. 3.3 (global sampling keeps tokens 0, omega, 2*omega, ...); 0 means T.
+ * Text tokens attend and are attended densely under every pattern and are never sampled by the ARM. */
+typedef struct {
+    float bw_spatial, bw_temporal;
+    int32_t tex_stride;
+    int32_t sample_interval;
+} rf_params;
+
+enum rf_head_class { RF_SPATIAL = 0, RF_TEMPORAL = 1, RF_TEXTURAL = 2, RF_DENSE = 3 };
+enum rf_sample_mode { RF_SAMPLE_FIRST_FRAME = 0, RF_SAMPLE_EQUAL_INTERVAL = 1 };
+enum rf_status {
+    RF_OK = 0,
+    RF_ERR_NULL = -1,      /* a required pointer is NULL */
+    RF_ERR_SHAPE = -2,     /* B, nH < 1, D not in {64, 96, 128}, or sizes overflow int32 token indices */
+    RF_ERR_LAYOUT = -3,    /* T, H, W < 1 or text_len < 0 */
+    RF_ERR_PARAM = -4,     /* bandwidth outside [0, 1], tex_stride < 1, sample_interval < 0, bad sample_mode,
+                              threshold not in [0, 1] or NaN */
+    RF_ERR_BLOCK = -5,     /* block not 64 or 128 */
+    RF_ERR_WORKSPACE = -6, /* workspace NULL or smaller than rf_arm_workspace_bytes() */
+    RF_ERR_HIP = -7        /* a HIP runtime call failed (allocation, copy or launch) */
+};
+
+/*
+ * ARM, Alg. 1: classify every head of one attention layer.
+ *   For each (b, h): R_hat = recall (Eq. 6) of the Temporal mask on the sampled Q', K'
+ *   (first-frame tokens in RF_SAMPLE_FIRST_FRAME mode, equal-interval tokens in
+ *   RF_SAMPLE_EQUAL_INTERVAL mode); R_tilde = recall of the Spatial mask on the
+ *   equal-interval sample.  Recall is the mean over sampled query rows of the softmax
+ *   mass (scores Q'K'^T / sqrt(D)) that falls on keys the mask keeps.
+ *   head_class = TEMPORAL if R_hat >= threshold, else SPATIAL if R_tilde >= threshold,
+ *   else TEXTURAL.
+ * Q, K        : device, bf16 [B, nH, N, D].
+ * head_class  : device, int32 [B*nH], written.
+ * recalls     : device, float [B*nH*2] = {R_hat, R_tilde} per head, written; may be NULL.
+ * workspace   : device scratch of at least rf_arm_workspace_bytes() bytes (per-row recalls;
+ *               contents undefined afterwards); two calls that overlap in time need two workspaces.
+ * The per-row recalls are reduced in a fixed order, so results are run-to-run identical.
+ */
+int rf_arm_classify(const void *Q, const void *K, int B, int nH, int D, const rf_layout *layout,
+                    const rf_params *params, int sample_mode, float threshold, int32_t *head_class,
+                    float *recalls, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of device scratch rf_arm_classify needs for this problem; 0 if the arguments are invalid. */
+size_t rf_arm_workspace_bytes(int B, int nH, const rf_layout *layout, const rf_params *params);
+
+/*
+ * Sparse attention forward, Eq. 1-2 with the mask of each head's pattern (Eq. 3-5):
+ *   O[b,h,i,:] = sum_j softmax_j(q_i . k_j / sqrt(D) over kept j) * v_j.
+ * The mask is token-level; `block` (64 or 128) only sets the granularity at which whole
+ * (query block, key block) pairs with no kept token pair are skipped, so O does not
+ * depend on it.  Scores and sums are accumulated in fp32, O is rounded to bf16.
+ * Q, K, V     : device, bf16 [B, nH, N, D].
+ * head_class  : device, int32 [B*nH], values of rf_head_class; read on the device, so the
+ *               output of rf_arm_classify can be passed on without a host round trip.
+ *               Values outside 0..3 are treated as RF_DENSE.
+ * O           : device, bf16 [B, nH, N, D], written.
+ */
+int rf_sparse_attention(const void *Q, const void *K, const void *V, const int32_t *head_class, int B,
+                        int nH, int D, const rf_layout *layout, const rf_params *params, int block,
+                        void *O, void *stream);
+
+/*
+ * Host-side view of the block list rf_sparse_attention walks (Fig. 2a "applying the sparse
+ * pattern"): for pattern `cls`, which key blocks each query block visits.  Pure host code,
+ * no GPU needed.
+ *   row_ptr : host, int32 [nQB + 1] (nQB = ceil(N / block)), written; may be NULL to only size.
+ *   cols    : host, int32 [cap]; entry = key-block index, plus RF_PLAN_PARTIAL if the pair
+ *             contains a dropped token pair or runs past the last token (the kernel applies the
+ *             token predicate there).  For RF_TEXTURAL, query blocks made only of video tokens
+ *             index blocks of the COMPACTED key sequence (kept keys in token order, then text).
+ *   needed  : host, receives the number of entries.
+ * Returns RF_ERR_WORKSPACE if cap < *needed (nothing but *needed is written then).
+ */
+#define RF_PLAN_PARTIAL 0x40000000
+int rf_plan_host(const rf_layout *layout, const rf_params *params, int block, int cls,
+                 int32_t *row_ptr, int32_t *cols, size_t cap, size_t *needed);
+
+/* Drop every cached block list and free its device memory (synchronises the device). */
+int rf_plan_clear(void);
+
+/* Human-readable name of a status code. Never NULL. */
+const char *rf_status_string(int status);
+
+/* Library version, major*100 + minor. */
+int rf_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAINFUSION_H */

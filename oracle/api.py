@@ -96,6 +96,8 @@ def _L():
         lib.rfo_arm_classify.argtypes = [f32p, f32p, C.c_int, PL, PP, C.c_int, C.c_double, f64p]
         lib.rfo_decide.restype = C.c_int
         lib.rfo_decide.argtypes = [C.c_double, C.c_double, C.c_double]
+        lib.rfo_keep_matrix.restype = None
+        lib.rfo_keep_matrix.argtypes = [C.c_int, PL, PP, C.POINTER(C.c_uint8)]
         lib.rfo_kept_fraction.restype = C.c_double
         lib.rfo_kept_fraction.argtypes = [C.c_int, PL, PP]
         _lib = lib
@@ -135,12 +137,9 @@ def keep(cls, i, j, L, P=Params()):
 def keep_matrix(cls, L, P=Params()):
     """Boolean [N, N] mask by calling the token predicate pair by pair (small N only)."""
     N = num_tokens(L)
-    lib, cl, cp = _L(), L.c(), P.c()
-    M = np.zeros((N, N), dtype=bool)
-    for i in range(N):
-        for j in range(N):
-            M[i, j] = lib.rfo_keep(cls, i, j, C.byref(cl), C.byref(cp))
-    return M
+    M = np.zeros((N, N), dtype=np.uint8)
+    _L().rfo_keep_matrix(cls, C.byref(L.c()), C.byref(P.c()), M.ctypes.data_as(C.POINTER(C.c_uint8)))
+    return M.astype(bool)
 
 
 def attention_rows(Q, K, V, cls, L, P, rows, want_prob=False):

@@ -285,3 +285,12 @@ double rfo_kept_fraction(int cls, const rfo_layout *L, const rfo_params *P)
         for (int64_t j = 0; j < N; ++j) kept += rfo_keep(cls, i, j, L, P);
     return (double)kept / ((double)N * (double)N);
 }
+
+/* The whole N x N mask of pattern cls as bytes (1 = kept), by calling the predicate pair by pair. */
+void rfo_keep_matrix(int cls, const rfo_layout *L, const rfo_params *P, uint8_t *out)
+{
+    const int64_t N = rfo_num_tokens(L);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < N; ++i)
+        for (int64_t j = 0; j < N; ++j) out[i * N + j] = (uint8_t)rfo_keep(cls, i, j, L, P);
+}

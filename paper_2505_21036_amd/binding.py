@@ -1,0 +1,179 @@
+"""ctypes binding of librainfusion.so: argument marshalling only.
+
+Every function has the name and meaning of the C entry point it wraps (see
+include/rainfusion.h).  Tensors are torch CUDA(HIP) tensors used purely as device
+memory; kernels are enqueued on torch's current stream.  There is no fallback: if the
+library has not been built, loading raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+RF_SPATIAL, RF_TEMPORAL, RF_TEXTURAL, RF_DENSE = 0, 1, 2, 3
+RF_SAMPLE_FIRST_FRAME, RF_SAMPLE_EQUAL_INTERVAL = 0, 1
+RF_PLAN_PARTIAL = 0x40000000
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "librainfusion.so")
+_lib = None
+
+
+class RfError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, rf_status_string(status), status))
+
+
+class rf_layout(C.Structure):
+    _fields_ = [("T", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("text_len", C.c_int32)]
+
+
+class rf_params(C.Structure):
+    _fields_ = [("bw_spatial", C.c_float), ("bw_temporal", C.c_float), ("tex_stride", C.c_int32),
+                ("sample_interval", C.c_int32)]
+
+    @classmethod
+    def default(cls):
+        return cls(0.25, 0.25, 2, 0)
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load librainfusion.so (built by paper_2505_21036_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError("librainfusion.so is not built: run `python -m paper_2505_21036_amd.build` "
+                           "(needs hipcc); there is no fallback path")
+    lib = C.CDLL(_LIB_PATH)
+    PL, PP, vp = C.POINTER(rf_layout), C.POINTER(rf_params), C.c_void_p
+    lib.rf_version.restype = C.c_int
+    lib.rf_version.argtypes = []
+    lib.rf_status_string.restype = C.c_char_p
+    lib.rf_status_string.argtypes = [C.c_int]
+    lib.rf_arm_workspace_bytes.restype = C.c_size_t
+    lib.rf_arm_workspace_bytes.argtypes = [C.c_int, C.c_int, PL, PP]
+    lib.rf_arm_classify.restype = C.c_int
+    lib.rf_arm_classify.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, PL, PP, C.c_int, C.c_float, vp, vp, vp,
+                                    C.c_size_t, vp]
+    lib.rf_sparse_attention.restype = C.c_int
+    lib.rf_sparse_attention.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, PL, PP, C.c_int, vp, vp]
+    lib.rf_plan_host.restype = C.c_int
+    lib.rf_plan_host.argtypes = [PL, PP, C.c_int, C.c_int, vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
+    lib.rf_plan_clear.restype = C.c_int
+    lib.rf_plan_clear.argtypes = []
+    _lib = lib
+    return lib
+
+
+def rf_version():
+    return load_library().rf_version()
+
+
+def rf_status_string(status):
+    return load_library().rf_status_string(status).decode()
+
+
+def _pp(params):
+    return None if params is None else C.byref(params)
+
+
+def rf_arm_workspace_bytes(B, nH, layout, params=None):
+    return load_library().rf_arm_workspace_bytes(B, nH, C.byref(layout), _pp(params))
+
+
+def _check_bf16(t, name, shape=None):
+    import torch
+    if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.dim() == 4):
+        raise ValueError("%s must be a contiguous bf16 device tensor [B, nH, N, D]" % name)
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s has shape %s, expected %s" % (name, tuple(t.shape), tuple(shape)))
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def rf_arm_classify(Q, K, layout, params=None, sample_mode=RF_SAMPLE_FIRST_FRAME, threshold=0.9,
+                    head_class=None, recalls=None, workspace=None):
+    """ARM (Alg. 1). Returns (head_class int32 [B, nH], recalls float32 [B, nH, 2]) on the device."""
+    import torch
+    _check_bf16(Q, "Q")
+    _check_bf16(K, "K", Q.shape)
+    B, nH, N, D = Q.shape
+    if N != layout.T * layout.H * layout.W + layout.text_len:
+        raise ValueError("N does not match the layout")
+    if head_class is None:
+        head_class = torch.empty(B, nH, dtype=torch.int32, device=Q.device)
+    if recalls is None:
+        recalls = torch.empty(B, nH, 2, dtype=torch.float32, device=Q.device)
+    need = rf_arm_workspace_bytes(B, nH, layout, params)
+    if workspace is None:
+        workspace = torch.empty(max(need, 4), dtype=torch.uint8, device=Q.device)
+    st = load_library().rf_arm_classify(Q.data_ptr(), K.data_ptr(), B, nH, D, C.byref(layout), _pp(params),
+                                        sample_mode, threshold, head_class.data_ptr(), recalls.data_ptr(),
+                                        workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                        _stream())
+    if st != 0:
+        raise RfError(st, "rf_arm_classify")
+    return head_class, recalls
+
+
+def rf_sparse_attention(Q, K, V, head_class, layout, params=None, block=128, out=None):
+    """Sparse attention forward (Eq. 1-5). head_class: int32 device tensor [B, nH]. Returns O."""
+    import torch
+    _check_bf16(Q, "Q")
+    _check_bf16(K, "K", Q.shape)
+    _check_bf16(V, "V", Q.shape)
+    B, nH, N, D = Q.shape
+    if N != layout.T * layout.H * layout.W + layout.text_len:
+        raise ValueError("N does not match the layout")
+    if not (head_class.is_cuda and head_class.dtype == torch.int32 and head_class.is_contiguous()
+            and head_class.numel() == B * nH):
+        raise ValueError("head_class must be a contiguous int32 device tensor with B*nH entries")
+    if out is None:
+        out = torch.empty_like(Q)
+    else:
+        _check_bf16(out, "out", Q.shape)
+    st = load_library().rf_sparse_attention(Q.data_ptr(), K.data_ptr(), V.data_ptr(), head_class.data_ptr(), B, nH,
+                                            D, C.byref(layout), _pp(params), block, out.data_ptr(), _stream())
+    if st != 0:
+        raise RfError(st, "rf_sparse_attention")
+    return out
+
+
+def rf_plan_host(layout, params, block, cls):
+    """Host copy of one class's block list: (row_ptr int32 [nQB+1], cols int32 [nnz])."""
+    lib = load_library()
+    N = layout.T * layout.H * layout.W + layout.text_len
+    nqb = (N + block - 1) // block
+    row_ptr = np.zeros(nqb + 1, dtype=np.int32)
+    needed = C.c_size_t(0)
+    st = lib.rf_plan_host(C.byref(layout), _pp(params), block, cls, row_ptr.ctypes.data, None, 0, C.byref(needed))
+    if st != 0:
+        raise RfError(st, "rf_plan_host")
+    cols = np.zeros(max(needed.value, 1), dtype=np.int32)
+    st = lib.rf_plan_host(C.byref(layout), _pp(params), block, cls, row_ptr.ctypes.data, cols.ctypes.data,
+                          cols.size, C.byref(needed))
+    if st != 0:
+        raise RfError(st, "rf_plan_host")
+    return row_ptr, cols[:needed.value]
+
+
+def plan_block_counts(layout, params, block, cls):
+    """(visited block pairs, of which partial, all block pairs) for one class: bookkeeping for FLOP counts."""
+    row_ptr, cols = rf_plan_host(layout, params, block, cls)
+    nqb = len(row_ptr) - 1
+    return int(len(cols)), int((cols & RF_PLAN_PARTIAL != 0).sum()), nqb * nqb
+
+
+def rf_plan_clear():
+    st = load_library().rf_plan_clear()
+    if st != 0:
+        raise RfError(st, "rf_plan_clear")

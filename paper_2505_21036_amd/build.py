@@ -1,0 +1,47 @@
+"""Builds librainfusion.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree."""
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "librainfusion.so")
+SOURCES = ["rf_api.cpp", "rf_plan.cpp", "rf_attn.hip", "rf_arm.hip"]
+HEADERS = ["rf_internal.h", "rf_device.h"]
+
+
+def hipcc():
+    for c in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
+        if c and (os.path.sep not in c or os.path.exists(c)):
+            return c
+    raise RuntimeError("hipcc not found")
+
+
+def build_library(verbose=False):
+    """Compile every source for gfx950 and link the shared library. Always rebuilds."""
+    objs = []
+    flags = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"),
+             "-I", CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
+             "-Wno-unused-command-line-argument"]
+    procs = []
+    for s in SOURCES:
+        obj = os.path.join(CSRC, os.path.splitext(s)[0] + ".o")
+        objs.append(obj)
+        procs.append((s, subprocess.Popen([hipcc()] + flags + ["-c", os.path.join(CSRC, s), "-o", obj],
+                                          stderr=subprocess.PIPE, text=True)))
+    for s, p in procs:
+        _, err = p.communicate()
+        err = "\n".join(l for l in err.splitlines() if "not a recognized feature" not in l)
+        if p.returncode != 0:
+            raise RuntimeError("hipcc failed on %s:\n%s" % (s, err))
+        if verbose and err.strip():
+            sys.stderr.write(err + "\n")
+    tmp = LIB + ".tmp%d" % os.getpid()
+    subprocess.check_call([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs)
+    os.replace(tmp, LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build_library(verbose=True))

@@ -1,0 +1,273 @@
+// C ABI of the RainFusion library: argument checks, the cache of device-resident block
+// lists, and the two entry points.  All checks run before the first HIP call, so they can
+// be exercised on a machine without a GPU.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <memory>
+#include <mutex>
+#include <vector>
+
+#include "rf_internal.h"
+
+namespace rf {
+namespace {
+
+struct CachedPlan {
+    Geometry g;
+    int block;  // 0 for the ARM sample tables
+    int device;
+    void* blob = nullptr;
+    DevicePlan dev{};
+    // ARM tables (block == 0)
+    const int32_t* local_pos = nullptr;   // [HW]   in-frame position of first-frame sample a
+    const int32_t* global_pos = nullptr;  // [nG]   in-frame position of equal-interval sample a
+    const int32_t* global_frame = nullptr;  // [nG] frame of equal-interval sample a
+    int nG = 0;
+};
+
+std::mutex g_mu;
+std::vector<std::unique_ptr<CachedPlan>> g_plans;
+
+bool same_geometry(const Geometry& a, const Geometry& b) { return std::memcmp(&a, &b, sizeof(Geometry)) == 0; }
+
+CachedPlan* find_plan(const Geometry& g, int block, int device) {
+    for (auto& p : g_plans)
+        if (p->block == block && p->device == device && same_geometry(p->g, g)) return p.get();
+    return nullptr;
+}
+
+// Uploads `words` and returns the device address; segments are 256-byte aligned inside one blob.
+struct BlobBuilder {
+    std::vector<int32_t> words;
+    size_t add(const std::vector<int32_t>& v) {
+        while (words.size() % 64) words.push_back(0);
+        const size_t off = words.size();
+        words.insert(words.end(), v.begin(), v.end());
+        if (v.empty()) words.push_back(0);
+        return off;
+    }
+    int upload(void** blob) {
+        if (hipMalloc(blob, words.size() * sizeof(int32_t)) != hipSuccess) return RF_ERR_HIP;
+        if (hipMemcpy(*blob, words.data(), words.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipFree(*blob);
+            *blob = nullptr;
+            return RF_ERR_HIP;
+        }
+        return RF_OK;
+    }
+};
+
+int get_attention_plan(const Geometry& g, int block, const DevicePlan** out) {
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return RF_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_mu);
+    CachedPlan* cp = find_plan(g, block, device);
+    if (!cp) {
+        HostPlan hp;
+        build_plan(g, block, &hp);
+        BlobBuilder bb;
+        size_t off_rp[3], off_co[3], off_at[3];
+        for (int c = 0; c < 3; ++c) {
+            off_rp[c] = bb.add(hp.row_ptr[c]);
+            off_co[c] = bb.add(hp.cols[c]);
+            off_at[c] = bb.add(hp.attr[c]);
+        }
+        const size_t off_ci = bb.add(hp.cidx);
+        auto p = std::make_unique<CachedPlan>();
+        p->g = g;
+        p->block = block;
+        p->device = device;
+        const int st = bb.upload(&p->blob);
+        if (st != RF_OK) return st;
+        const int32_t* base = static_cast<const int32_t*>(p->blob);
+        DevicePlan& d = p->dev;
+        for (int c = 0; c < 3; ++c) {
+            d.row_ptr[c] = base + off_rp[c];
+            d.cols[c] = base + off_co[c];
+            d.attr[c] = base + off_at[c];
+        }
+        d.cidx = base + off_ci;
+        d.radius[RF_SPATIAL] = g.r_spatial;
+        d.radius[RF_TEMPORAL] = g.r_temporal;
+        d.radius[RF_TEXTURAL] = 0;
+        d.N = g.N; d.Nv = g.Nv; d.Nc = hp.Nc;
+        d.block = block; d.nQB = hp.nQB; d.nKB = hp.nKB; d.nCB = hp.nCB;
+        d.first_text_qb = hp.first_text_qb;
+        cp = p.get();
+        g_plans.push_back(std::move(p));
+    }
+    *out = &cp->dev;
+    return RF_OK;
+}
+
+int global_sample_count(const Geometry& g) { return (g.Nv + g.omega - 1) / g.omega; }
+
+int get_arm_tables(const Geometry& g, const CachedPlan** out) {
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return RF_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_mu);
+    CachedPlan* cp = find_plan(g, 0, device);
+    if (!cp) {
+        const int nG = global_sample_count(g);
+        std::vector<int32_t> lp(g.HW), gp(nG), gf(nG);
+        for (int a = 0; a < g.HW; ++a) lp[a] = a;
+        for (int a = 0; a < nG; ++a) {
+            const int64_t tok = static_cast<int64_t>(a) * g.omega;
+            gp[a] = static_cast<int32_t>(tok % g.HW);
+            gf[a] = static_cast<int32_t>(tok / g.HW);
+        }
+        BlobBuilder bb;
+        const size_t o0 = bb.add(lp), o1 = bb.add(gp), o2 = bb.add(gf);
+        auto p = std::make_unique<CachedPlan>();
+        p->g = g;
+        p->block = 0;
+        p->device = device;
+        const int st = bb.upload(&p->blob);
+        if (st != RF_OK) return st;
+        const int32_t* base = static_cast<const int32_t*>(p->blob);
+        p->local_pos = base + o0;
+        p->global_pos = base + o1;
+        p->global_frame = base + o2;
+        p->nG = nG;
+        cp = p.get();
+        g_plans.push_back(std::move(p));
+    }
+    *out = cp;
+    return RF_OK;
+}
+
+int check_shape(int B, int nH, int D, const Geometry& g) {
+    if (B < 1 || nH < 1) return RF_ERR_SHAPE;
+    if (D != 64 && D != 96 && D != 128) return RF_ERR_SHAPE;
+    if (static_cast<int64_t>(B) * nH > (1 << 20)) return RF_ERR_SHAPE;
+    (void)g;
+    return RF_OK;
+}
+
+size_t arm_rows(const Geometry& g) { return static_cast<size_t>(std::max(g.HW, global_sample_count(g))); }
+
+}  // namespace
+}  // namespace rf
+
+using namespace rf;
+
+extern "C" {
+
+int rf_version(void) { return 100; }
+
+const char* rf_status_string(int status) {
+    switch (status) {
+        case RF_OK: return "ok";
+        case RF_ERR_NULL: return "null pointer";
+        case RF_ERR_SHAPE: return "bad tensor shape";
+        case RF_ERR_LAYOUT: return "bad video layout";
+        case RF_ERR_PARAM: return "bad parameter";
+        case RF_ERR_BLOCK: return "block must be 64 or 128";
+        case RF_ERR_WORKSPACE: return "workspace missing or too small";
+        case RF_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+size_t rf_arm_workspace_bytes(int B, int nH, const rf_layout* layout, const rf_params* params) {
+    Geometry g;
+    if (resolve_geometry(layout, params, &g) != RF_OK || B < 1 || nH < 1) return 0;
+    return static_cast<size_t>(B) * nH * 2 * arm_rows(g) * sizeof(float);
+}
+
+int rf_arm_classify(const void* Q, const void* K, int B, int nH, int D, const rf_layout* layout,
+                    const rf_params* params, int sample_mode, float threshold, int32_t* head_class,
+                    float* recalls, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!Q || !K || !head_class || !layout) return RF_ERR_NULL;
+    Geometry g;
+    int st = resolve_geometry(layout, params, &g);
+    if (st != RF_OK) return st;
+    st = check_shape(B, nH, D, g);
+    if (st != RF_OK) return st;
+    if (sample_mode != RF_SAMPLE_FIRST_FRAME && sample_mode != RF_SAMPLE_EQUAL_INTERVAL) return RF_ERR_PARAM;
+    if (!(threshold >= 0.f && threshold <= 1.f)) return RF_ERR_PARAM;
+    if (!workspace || workspace_bytes < rf_arm_workspace_bytes(B, nH, layout, params)) return RF_ERR_WORKSPACE;
+
+    const CachedPlan* tb = nullptr;
+    st = get_arm_tables(g, &tb);
+    if (st != RF_OK) return st;
+
+    ArmArgs a{};
+    a.Q = static_cast<const uint16_t*>(Q);
+    a.K = static_cast<const uint16_t*>(K);
+    a.BH = B * nH;
+    a.N = g.N;
+    a.scale_log2 = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(D)));
+    if (sample_mode == RF_SAMPLE_FIRST_FRAME) a.pass[0] = ArmPass{tb->local_pos, g.HW, 1, g.r_temporal};
+    else a.pass[0] = ArmPass{tb->global_pos, tb->nG, g.omega, g.r_temporal};
+    a.pass[1] = ArmPass{tb->global_frame, tb->nG, g.omega, g.r_spatial};
+    a.row_recall = static_cast<float*>(workspace);
+    a.max_n = static_cast<int>(arm_rows(g));
+    a.threshold = threshold;
+    a.head_class = head_class;
+    a.recalls = recalls;
+    return launch_arm(a, D, stream) == 0 ? RF_OK : RF_ERR_HIP;
+}
+
+int rf_sparse_attention(const void* Q, const void* K, const void* V, const int32_t* head_class, int B, int nH,
+                        int D, const rf_layout* layout, const rf_params* params, int block, void* O,
+                        void* stream) {
+    if (!Q || !K || !V || !O || !head_class || !layout) return RF_ERR_NULL;
+    Geometry g;
+    int st = resolve_geometry(layout, params, &g);
+    if (st != RF_OK) return st;
+    st = check_shape(B, nH, D, g);
+    if (st != RF_OK) return st;
+    if (block != 64 && block != 128) return RF_ERR_BLOCK;
+
+    const DevicePlan* dp = nullptr;
+    st = get_attention_plan(g, block, &dp);
+    if (st != RF_OK) return st;
+
+    AttnArgs a{};
+    a.Q = static_cast<const uint16_t*>(Q);
+    a.K = static_cast<const uint16_t*>(K);
+    a.V = static_cast<const uint16_t*>(V);
+    a.O = static_cast<uint16_t*>(O);
+    a.head_class = head_class;
+    a.BH = B * nH;
+    a.scale_log2 = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(D)));
+    a.plan = *dp;
+    return launch_attention(a, D, stream) == 0 ? RF_OK : RF_ERR_HIP;
+}
+
+int rf_plan_host(const rf_layout* layout, const rf_params* params, int block, int cls, int32_t* row_ptr,
+                 int32_t* cols, size_t cap, size_t* needed) {
+    if (!layout || !needed) return RF_ERR_NULL;
+    Geometry g;
+    const int st = resolve_geometry(layout, params, &g);
+    if (st != RF_OK) return st;
+    if (block != 64 && block != 128) return RF_ERR_BLOCK;
+    if (cls < RF_SPATIAL || cls > RF_DENSE) return RF_ERR_PARAM;
+    HostPlan hp;
+    build_plan(g, block, &hp);
+    std::vector<int32_t> rp, co;
+    flatten_class(hp, cls, &rp, &co);
+    *needed = co.size();
+    if (row_ptr) std::memcpy(row_ptr, rp.data(), rp.size() * sizeof(int32_t));
+    if (cols) {
+        if (cap < co.size()) return RF_ERR_WORKSPACE;
+        std::memcpy(cols, co.data(), co.size() * sizeof(int32_t));
+    }
+    return RF_OK;
+}
+
+int rf_plan_clear(void) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (g_plans.empty()) return RF_OK;
+    int st = RF_OK;
+    if (hipDeviceSynchronize() != hipSuccess) st = RF_ERR_HIP;
+    for (auto& p : g_plans)
+        if (p->blob && hipFree(p->blob) != hipSuccess) st = RF_ERR_HIP;
+    g_plans.clear();
+    return st;
+}
+
+}  // extern "C"

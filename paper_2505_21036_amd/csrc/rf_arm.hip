@@ -1,0 +1,158 @@
+// ARM head classifier (Sec. 3.3, Eq. 6, Alg. 1) on gfx950.
+//
+// Pass 0 measures the recall of the Temporal mask (R-hat), pass 1 that of the Spatial mask
+// (R-tilde).  A pass is described by its sample (sample a is token a * stride), an integer
+// attribute per sample (in-frame position, resp. frame index) and a radius: the mask keeps
+// |attr[a] - attr[b]| <= radius.  The scores Q'K'^T / sqrt(D) are formed tile by tile with
+// bf16 MFMA and never stored; per sampled query the kernel keeps a running maximum, the
+// softmax denominator over all sampled keys (M_init) and the part of it on kept keys (M').
+// Per-row recalls go to scratch and are reduced in a fixed order by arm_finish_kernel, which
+// also applies the decision rule.
+#include "rf_device.h"
+
+namespace rf {
+
+constexpr int kArmWaves = 4;  // 128 sampled queries per workgroup
+
+template <int D>
+__global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, int nQB) {
+    constexpr int NW = kArmWaves, NT = 64 * NW, BQ = 32 * NW;
+    using KT = KTile<D, NT>;
+    __shared__ __attribute__((aligned(16))) unsigned char kbuf[2 * KT::BYTES];
+    __shared__ int abuf[2 * kTileK];
+
+    const int item = xcd_contiguous_item(blockIdx.x, nQB * 2 * a.BH);
+    if (item < 0) return;
+    const int qb = item % nQB, pass = (item / nQB) & 1, bh = item / (2 * nQB);
+    const ArmPass ps = a.pass[pass];
+    const int n = ps.n;
+    if (qb * BQ >= n) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, m = lane & 31;
+
+    const size_t head_off = static_cast<size_t>(bh) * a.N * D;
+    const uint16_t* Qh = a.Q + head_off;
+    const uint16_t* Kh = a.K + head_off;
+
+    const int qs = qb * BQ + wave * 32 + m;  // this lane's sampled query
+    const int qsc = min(qs, n - 1);
+    bf16x8 qf[D / 16];
+    load_q_frags<D>(Qh, qsc * ps.stride, hf, qf);
+    const int q_attr = ps.attr[qsc];
+
+    float m_run = -INFINITY, l_all = 0.f, l_kept = 0.f;
+    const float c = a.scale_log2;
+    const int ntiles = (n + kTileK - 1) / kTileK;
+
+    KT kt;
+    int attr_reg = 0;
+    auto fetch_tile = [&](int t) {
+        const int k0 = t * kTileK;
+        kt.fetch(Kh, tid, [&](int r) { return min(k0 + r, n - 1) * ps.stride; });
+        if (tid < kTileK) attr_reg = ps.attr[min(k0 + tid, n - 1)];
+    };
+    auto stash_tile = [&](int t) {
+        kt.stash(kbuf + (t & 1) * KT::BYTES, tid);
+        if (tid < kTileK) abuf[(t & 1) * kTileK + tid] = attr_reg;
+    };
+    fetch_tile(0);
+    stash_tile(0);
+    __syncthreads();
+
+    for (int t = 0; t < ntiles; ++t) {
+        if (t + 1 < ntiles) fetch_tile(t + 1);
+        const unsigned char* kl = kbuf + (t & 1) * KT::BYTES;
+        const int* al = abuf + (t & 1) * kTileK;
+        const int k0 = t * kTileK;
+
+        f32x16 s[2];
+        score_tile<D, NT>(kl, qf, m, hf, s);
+        if (k0 + kTileK > n) {  // ragged last tile: samples past the end do not exist
+#pragma unroll
+            for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (k0 + 32 * kb2 + key_of_reg(r, hf) >= n) s[kb2][r] = -INFINITY;
+        }
+        float mt = s[0][0];
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mt = fmaxf(mt, s[kb2][r]);
+        mt = fmaxf(mt, other_half(mt));
+        const float m_new = fmaxf(m_run, mt);  // finite: every tile holds at least one real sample
+        const float alpha = fast_exp2((m_run - m_new) * c);
+        const float mc = m_new * c;
+        float sum_all = 0.f, sum_kept = 0.f;
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = fast_exp2(fmaf(s[kb2][r], c, -mc));
+                const int d = q_attr - al[32 * kb2 + key_of_reg(r, hf)];
+                sum_all += p;
+                sum_kept += ((d < 0 ? -d : d) <= ps.radius) ? p : 0.f;
+            }
+        l_all = l_all * alpha + sum_all;
+        l_kept = l_kept * alpha + sum_kept;
+        m_run = m_new;
+
+        if (t + 1 < ntiles) stash_tile(t + 1);
+        __syncthreads();
+    }
+    l_all += other_half(l_all);
+    l_kept += other_half(l_kept);
+    if (hf == 0 && qs < n)
+        a.row_recall[(static_cast<size_t>(bh) * 2 + pass) * a.max_n + qs] = l_kept / l_all;  // Eq. 6, one row
+}
+
+// Mean of the per-row recalls in a fixed summation order, then Alg. 1's rule.
+__global__ void __launch_bounds__(256) arm_finish_kernel(ArmArgs a) {
+    __shared__ float red[256];
+    const int bh = blockIdx.x, tid = threadIdx.x;
+    float rec[2];
+    for (int pass = 0; pass < 2; ++pass) {
+        const int n = a.pass[pass].n;
+        const float* rr = a.row_recall + (static_cast<size_t>(bh) * 2 + pass) * a.max_n;
+        float acc = 0.f;
+        for (int i = tid; i < n; i += 256) acc += rr[i];
+        red[tid] = acc;
+        __syncthreads();
+        for (int w = 128; w > 0; w >>= 1) {
+            if (tid < w) red[tid] += red[tid + w];
+            __syncthreads();
+        }
+        rec[pass] = red[0] / static_cast<float>(n);
+        __syncthreads();
+    }
+    if (tid == 0) {
+        int cls = RF_TEXTURAL;
+        if (rec[0] >= a.threshold) cls = RF_TEMPORAL;  // Temporal has priority
+        else if (rec[1] >= a.threshold) cls = RF_SPATIAL;
+        a.head_class[bh] = cls;
+        if (a.recalls) {
+            a.recalls[2 * bh] = rec[0];
+            a.recalls[2 * bh + 1] = rec[1];
+        }
+    }
+}
+
+template <int D>
+static int launch_arm_d(const ArmArgs& a, hipStream_t st) {
+    const int nQB = (a.max_n + 32 * kArmWaves - 1) / (32 * kArmWaves);
+    const int total = nQB * 2 * a.BH;
+    hipLaunchKernelGGL((arm_recall_kernel<D>), dim3(8 * ((total + 7) / 8)), dim3(64 * kArmWaves), 0, st, a, nQB);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return static_cast<int>(e);
+    hipLaunchKernelGGL(arm_finish_kernel, dim3(a.BH), dim3(256), 0, st, a);
+    return static_cast<int>(hipGetLastError());
+}
+
+int launch_arm(const ArmArgs& a, int D, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (D == 64) return launch_arm_d<64>(a, st);
+    if (D == 96) return launch_arm_d<96>(a, st);
+    if (D == 128) return launch_arm_d<128>(a, st);
+    return static_cast<int>(hipErrorInvalidValue);
+}
+
+}  // namespace rf

@@ -1,0 +1,94 @@
+// Internal declarations shared by the host side (argument checks, block lists) and the
+// HIP kernels of the RainFusion library.  Not part of the public ABI.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "rainfusion.h"
+
+namespace rf {
+
+constexpr int kTileK = 64;  // keys per LDS tile of the attention and ARM kernels
+
+// Resolved, validated problem description.
+struct Geometry {
+    int T, H, W, text_len;
+    int HW, Nv, N;
+    int r_spatial, r_temporal;  // band half-widths in frames / in-frame positions
+    int tau;                    // checkerboard stride (Eq. 4)
+    int omega;                  // global sampling interval (Sec. 3.3)
+};
+
+// Host copy of everything the attention kernel needs besides the tensors.
+// Index 0/1/2 of the per-class arrays = Spatial / Temporal / Textural.
+struct HostPlan {
+    Geometry g;
+    int block;     // skip-list granularity (64 or 128), also the query rows per workgroup
+    int nQB, nKB;  // ceil(N / block)
+    int Nc;        // compacted key count of the Textural pattern: kept video keys + text keys
+    int nCB;       // ceil(Nc / block)
+    int first_text_qb;  // first query block holding a text row (nQB if there is none)
+    std::vector<int32_t> row_ptr[3], cols[3];  // CSR block lists; Textural: text-holding query blocks only
+    std::vector<int32_t> attr[3];  // per token: frame index / in-frame index / 0 if kept by Eq. 4 else 1
+    std::vector<int32_t> cidx;     // compacted position -> token index (Textural)
+};
+
+// Fills g from layout/params (params may be null -> paper defaults). Returns an rf_status.
+int resolve_geometry(const rf_layout* layout, const rf_params* params, Geometry* g);
+
+// Builds the block lists. Pure host code.
+void build_plan(const Geometry& g, int block, HostPlan* plan);
+
+// Block list of one class as the kernel walks it (see rf_plan_host in rainfusion.h).
+void flatten_class(const HostPlan& plan, int cls, std::vector<int32_t>* row_ptr, std::vector<int32_t>* cols);
+
+// Device-resident plan: raw device pointers into one allocation.
+struct DevicePlan {
+    const int32_t* row_ptr[3];
+    const int32_t* cols[3];
+    const int32_t* attr[3];
+    const int32_t* cidx;
+    int radius[3];
+    int N, Nv, Nc;
+    int block, nQB, nKB, nCB, first_text_qb;
+};
+
+struct AttnArgs {
+    const uint16_t* Q;
+    const uint16_t* K;
+    const uint16_t* V;
+    uint16_t* O;
+    const int32_t* head_class;
+    int BH;            // B * nH
+    float scale_log2;  // log2(e) / sqrt(D)
+    DevicePlan plan;
+};
+
+// One ARM pass = one (sampling, mask) pair: sample a -> token a * stride, mask keeps
+// |attr[a] - attr[b]| <= radius.
+struct ArmPass {
+    const int32_t* attr;  // device [n]
+    int n;                // number of samples
+    int stride;           // token stride between samples
+    int radius;
+};
+
+struct ArmArgs {
+    const uint16_t* Q;
+    const uint16_t* K;
+    int BH, N;
+    float scale_log2;
+    ArmPass pass[2];   // 0: Temporal mask (R_hat), 1: Spatial mask (R_tilde)
+    float* row_recall; // device [BH][2][max_n]
+    int max_n;
+    float threshold;
+    int32_t* head_class;  // device [BH]
+    float* recalls;       // device [BH*2] or null
+};
+
+// Kernel launchers (defined in the .hip files). Return a hipError_t as int.
+int launch_attention(const AttnArgs& a, int D, void* stream);
+int launch_arm(const ArmArgs& a, int D, void* stream);
+
+}  // namespace rf

@@ -1,0 +1,153 @@
+// Host-side block lists for RainFusion's three head patterns (Sec. 3.2).
+//
+// The masks are token-level predicates; this file only decides, for a square tiling of the
+// N x N score matrix, which (query block, key block) pairs contain at least one kept pair
+// (they are visited) and which of those contain a dropped pair or run past the last token
+// (the kernel re-applies the predicate there).  Everything is exact integer interval
+// arithmetic on frame indices and in-frame positions.
+#include <algorithm>
+#include <cmath>
+#include <utility>
+
+#include "rf_internal.h"
+
+namespace rf {
+
+static int band_radius(float bw, int n) {
+    double r = std::floor(static_cast<double>(bw) * static_cast<double>(n));
+    if (r < 0) r = 0;
+    if (r > n) r = n;
+    return static_cast<int>(r);
+}
+
+int resolve_geometry(const rf_layout* L, const rf_params* P, Geometry* g) {
+    if (!L) return RF_ERR_NULL;
+    if (L->T < 1 || L->H < 1 || L->W < 1 || L->text_len < 0) return RF_ERR_LAYOUT;
+    const int64_t HW = static_cast<int64_t>(L->H) * L->W;
+    const int64_t Nv = HW * L->T;
+    const int64_t N = Nv + L->text_len;
+    if (N > (int64_t{1} << 24)) return RF_ERR_SHAPE;  // keeps every index and block count in int32
+    rf_params def = {0.25f, 0.25f, 2, 0};
+    const rf_params* p = P ? P : &def;
+    if (!(p->bw_spatial >= 0.f && p->bw_spatial <= 1.f)) return RF_ERR_PARAM;
+    if (!(p->bw_temporal >= 0.f && p->bw_temporal <= 1.f)) return RF_ERR_PARAM;
+    if (p->tex_stride < 1 || p->sample_interval < 0) return RF_ERR_PARAM;
+    g->T = L->T; g->H = L->H; g->W = L->W; g->text_len = L->text_len;
+    g->HW = static_cast<int>(HW); g->Nv = static_cast<int>(Nv); g->N = static_cast<int>(N);
+    g->r_spatial = band_radius(p->bw_spatial, L->T);
+    g->r_temporal = band_radius(p->bw_temporal, g->HW);
+    g->tau = p->tex_stride;
+    g->omega = p->sample_interval > 0 ? p->sample_interval : L->T;
+    return RF_OK;
+}
+
+namespace {
+
+struct Span { int lo, hi; };  // inclusive
+
+// In-frame positions covered by video tokens [s, e): one span per frame touched.
+void position_spans(int s, int e, int HW, std::vector<Span>* out) {
+    out->clear();
+    if (s >= e) return;
+    const int fs = s / HW, fe = (e - 1) / HW;
+    for (int f = fs; f <= fe; ++f) {
+        Span sp{f == fs ? s % HW : 0, f == fe ? (e - 1) % HW : HW - 1};
+        out->push_back(sp);
+        if (sp.lo == 0 && sp.hi == HW - 1) { out->assign(1, sp); return; }  // a whole frame covers all
+    }
+}
+
+inline int span_gap(Span a, Span b) { return std::max(0, std::max(b.lo - a.hi, a.lo - b.hi)); }
+inline int span_reach(Span a, Span b) { return std::max(b.hi - a.lo, a.hi - b.lo); }
+
+}  // namespace
+
+void build_plan(const Geometry& g, int block, HostPlan* plan) {
+    HostPlan& P = *plan;
+    P.g = g;
+    P.block = block;
+    const int N = g.N, Nv = g.Nv, HW = g.HW;
+    P.nQB = P.nKB = (N + block - 1) / block;
+    P.first_text_qb = g.text_len > 0 ? Nv / block : P.nQB;
+
+    // per-token attributes
+    for (auto& a : P.attr) a.assign(N, 0);
+    P.cidx.clear();
+    for (int n = 0; n < Nv; ++n) {
+        const int f = n / HW, p = n % HW, y = p / g.W, x = p % g.W;
+        P.attr[RF_SPATIAL][n] = f;
+        P.attr[RF_TEMPORAL][n] = p;
+        const bool kept = ((y - x) % g.tau) == 0;
+        P.attr[RF_TEXTURAL][n] = kept ? 0 : 1;
+        if (kept) P.cidx.push_back(n);
+    }
+    for (int n = Nv; n < N; ++n) P.cidx.push_back(n);
+    P.Nc = static_cast<int>(P.cidx.size());
+    P.nCB = (P.Nc + block - 1) / block;
+
+    std::vector<Span> qs, ks;
+    for (int cls = 0; cls < 3; ++cls) {
+        auto& rp = P.row_ptr[cls];
+        auto& co = P.cols[cls];
+        rp.assign(P.nQB + 1, 0);
+        co.clear();
+        for (int qb = 0; qb < P.nQB; ++qb) {
+            const int q0 = qb * block, q1 = std::min(N, q0 + block);
+            const int qv1 = std::min(q1, Nv);  // video part [q0, qv1)
+            const bool q_text = q1 > Nv, q_video = q0 < Nv;
+            if (cls == RF_TEXTURAL && !q_text) { rp[qb + 1] = static_cast<int32_t>(co.size()); continue; }
+            if (cls == RF_TEMPORAL && q_video) position_spans(q0, qv1, HW, &qs);
+            for (int kb = 0; kb < P.nKB; ++kb) {
+                const int k0 = kb * block, k1 = std::min(N, k0 + block);
+                const int kv1 = std::min(k1, Nv);
+                const bool k_text = k1 > Nv, k_video = k0 < Nv;
+                bool any = q_text || k_text, all = true;
+                if (q_video && k_video) {
+                    if (cls == RF_SPATIAL) {
+                        Span a{q0 / HW, (qv1 - 1) / HW}, b{k0 / HW, (kv1 - 1) / HW};
+                        any = any || span_gap(a, b) <= g.r_spatial;
+                        all = span_reach(a, b) <= g.r_spatial;
+                    } else if (cls == RF_TEMPORAL) {
+                        position_spans(k0, kv1, HW, &ks);
+                        for (Span a : qs)
+                            for (Span b : ks) {
+                                any = any || span_gap(a, b) <= g.r_temporal;
+                                all = all && span_reach(a, b) <= g.r_temporal;
+                            }
+                    } else {  // Textural rows of a block that also holds text rows
+                        bool every_kept = true, some_kept = false;
+                        for (int j = k0; j < kv1; ++j) {
+                            const bool kept = P.attr[RF_TEXTURAL][j] == 0;
+                            every_kept = every_kept && kept;
+                            some_kept = some_kept || kept;
+                        }
+                        any = any || some_kept;
+                        all = every_kept;
+                    }
+                }
+                if (!any) continue;
+                const bool tail = k0 + block > N;
+                co.push_back(kb | ((!all || tail) ? RF_PLAN_PARTIAL : 0));
+            }
+            rp[qb + 1] = static_cast<int32_t>(co.size());
+        }
+    }
+}
+
+void flatten_class(const HostPlan& P, int cls, std::vector<int32_t>* row_ptr, std::vector<int32_t>* cols) {
+    row_ptr->assign(P.nQB + 1, 0);
+    cols->clear();
+    for (int qb = 0; qb < P.nQB; ++qb) {
+        if (cls == RF_DENSE || (cls == RF_TEXTURAL && qb < P.first_text_qb)) {
+            const int nb = cls == RF_DENSE ? P.nKB : P.nCB;
+            const int len = cls == RF_DENSE ? P.g.N : P.Nc;
+            for (int kb = 0; kb < nb; ++kb)
+                cols->push_back(kb | ((kb + 1) * P.block > len ? RF_PLAN_PARTIAL : 0));
+        } else {
+            for (int e = P.row_ptr[cls][qb]; e < P.row_ptr[cls][qb + 1]; ++e) cols->push_back(P.cols[cls][e]);
+        }
+        (*row_ptr)[qb + 1] = static_cast<int32_t>(cols->size());
+    }
+}
+
+}  // namespace rf

@@ -1,0 +1,145 @@
+"""Host logic of the library, no GPU: the block lists against a brute-force scan of the
+oracle's token predicate, the exported symbols against the header, and argument checks."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle as orc
+import paper_2505_21036_amd as rf
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+LAYOUTS = [
+    (4, 8, 8, 0),      # tiny: block 64 == one frame
+    (5, 6, 11, 19),    # frames of 66 tokens straddle 64-blocks, text tail
+    (3, 20, 23, 70),   # frames of 460 tokens, text spans more than one 64-block
+    (7, 10, 13, 50),
+    (2, 5, 5, 0),      # frames smaller than a block
+    (9, 3, 3, 200),    # mostly text
+]
+PARAMS = [(0.25, 0.25, 2), (0.13, 0.18, 3), (0.0, 0.0, 4), (1.0, 1.0, 1), (0.4, 0.05, 2)]
+
+
+def brute_blocks(M, block):
+    """(any, all-and-no-tail) per block pair from an explicit boolean mask."""
+    N = M.shape[0]
+    nb = -(-N // block)
+    pad = np.zeros((nb * block, nb * block), dtype=bool)
+    pad[:N, :N] = M
+    t = pad.reshape(nb, block, nb, block)
+    any_ = t.any(axis=(1, 3))
+    # "full" means every existing query row keeps every key slot of the block, tail slots included
+    rows = np.zeros(nb * block, dtype=bool)
+    rows[:N] = True
+    full = np.ones((nb, nb), dtype=bool)
+    for qb in range(nb):
+        r = rows[qb * block:(qb + 1) * block]
+        full[qb] = t[qb][r].all(axis=(0, 2))
+    return any_, full
+
+
+@pytest.mark.parametrize("lay", LAYOUTS)
+@pytest.mark.parametrize("par", PARAMS)
+@pytest.mark.parametrize("block", [64, 128])
+def test_block_lists_match_brute_force(lay, par, block):
+    L, P = orc.Layout(*lay), orc.Params(par[0], par[1], par[2])
+    rl, rp = rf.rf_layout(*lay), rf.rf_params(par[0], par[1], par[2], 0)
+    N = orc.num_tokens(L)
+    nb = -(-N // block)
+    for cls in (orc.SPATIAL, orc.TEMPORAL, orc.DENSE):
+        any_, full = brute_blocks(orc.keep_matrix(cls, L, P), block)
+        row_ptr, cols = rf.rf_plan_host(rl, rp, block, cls)
+        assert len(row_ptr) == nb + 1 and row_ptr[0] == 0
+        for qb in range(nb):
+            ent = cols[row_ptr[qb]:row_ptr[qb + 1]]
+            kbs = ent & ~rf.RF_PLAN_PARTIAL
+            assert (np.diff(kbs) > 0).all()
+            assert set(kbs.tolist()) == set(np.nonzero(any_[qb])[0].tolist())  # visited == has a kept pair
+            partial = (ent & rf.RF_PLAN_PARTIAL) != 0
+            assert (partial == ~full[qb, kbs]).all()  # predicate re-applied exactly where needed
+
+
+@pytest.mark.parametrize("lay", LAYOUTS)
+@pytest.mark.parametrize("tau", [1, 2, 3])
+@pytest.mark.parametrize("block", [64, 128])
+def test_textural_lists(lay, tau, block):
+    """Video-only query blocks walk the compacted key sequence; blocks holding text rows walk token space."""
+    L, P = orc.Layout(*lay), orc.Params(0.25, 0.25, tau)
+    rl, rp = rf.rf_layout(*lay), rf.rf_params(0.25, 0.25, tau, 0)
+    N, Nv = orc.num_tokens(L), lay[0] * lay[1] * lay[2]
+    nb = -(-N // block)
+    M = orc.keep_matrix(orc.TEXTURAL, L, P)
+    Nc = int(M[0].sum()) if Nv > 0 else N
+    any_, full = brute_blocks(M, block)
+    row_ptr, cols = rf.rf_plan_host(rl, rp, block, orc.TEXTURAL)
+    for qb in range(nb):
+        ent = cols[row_ptr[qb]:row_ptr[qb + 1]]
+        kbs, partial = ent & ~rf.RF_PLAN_PARTIAL, (ent & rf.RF_PLAN_PARTIAL) != 0
+        if (qb + 1) * block <= Nv and not (lay[3] > 0 and qb >= Nv // block):
+            ncb = -(-Nc // block)
+            assert kbs.tolist() == list(range(ncb))
+            assert partial.tolist() == [(kb + 1) * block > Nc for kb in range(ncb)]
+        else:
+            assert set(kbs.tolist()) == set(np.nonzero(any_[qb])[0].tolist())
+            assert (partial == ~full[qb, kbs]).all()
+
+
+def test_paper_shapes_executed_fractions():
+    """At the 720p shape with block 128 about half of the block pairs are visited per pattern."""
+    rl = rf.rf_layout(33, 45, 80, 256)
+    for cls, lo, hi in ((rf.RF_SPATIAL, 0.44, 0.47), (rf.RF_TEMPORAL, 0.49, 0.53), (rf.RF_TEXTURAL, 0.49, 0.52)):
+        vis, part, tot = rf.plan_block_counts(rl, None, 128, cls)
+        assert lo < vis / tot < hi, (cls, vis / tot)
+    vis, part, tot = rf.plan_block_counts(rl, None, 128, rf.RF_DENSE)
+    assert vis == tot and part == 931
+
+
+def test_every_declared_symbol_is_exported():
+    lib = rf.load_library()
+    hdr = open(os.path.join(ROOT, "include", "rainfusion.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = re.findall(r"\b(rf_[a-z_]+)\s*\(", hdr)
+    assert set(names) >= {"rf_arm_classify", "rf_sparse_attention", "rf_arm_workspace_bytes", "rf_plan_host",
+                          "rf_plan_clear", "rf_status_string", "rf_version"}
+    for n in set(names):
+        assert getattr(lib, n) is not None
+    assert rf.rf_version() >= 100
+    assert rf.rf_status_string(0) == "ok" and "block" in rf.rf_status_string(-5)
+
+
+def test_bad_arguments_are_rejected_before_any_gpu_work():
+    lib = rf.load_library()
+    L = rf.rf_layout(4, 8, 8, 0)
+    one = C.c_void_p(16)  # non-null dummy; never dereferenced because validation fails first
+    ok_p = rf.rf_params.default()
+
+    def attn(Q=one, K=one, V=one, hc=one, B=1, nH=2, D=64, lay=L, par=ok_p, block=64, O=one):
+        return lib.rf_sparse_attention(Q, K, V, hc, B, nH, D, C.byref(lay) if lay else None,
+                                       C.byref(par) if par else None, block, O, None)
+
+    assert attn(Q=None) == -1 and attn(O=None) == -1 and attn(hc=None) == -1 and attn(lay=None) == -1
+    assert attn(D=80) == -2 and attn(B=0) == -2 and attn(nH=-1) == -2
+    assert attn(lay=rf.rf_layout(0, 8, 8, 0)) == -3 and attn(lay=rf.rf_layout(4, 8, 8, -1)) == -3
+    assert attn(lay=rf.rf_layout(4096, 4096, 4096, 0)) in (-2, -3)
+    assert attn(par=rf.rf_params(1.5, 0.25, 2, 0)) == -4 and attn(par=rf.rf_params(0.25, -0.1, 2, 0)) == -4
+    assert attn(par=rf.rf_params(0.25, 0.25, 0, 0)) == -4 and attn(par=rf.rf_params(float("nan"), 0.25, 2, 0)) == -4
+    assert attn(block=32) == -5 and attn(block=256) == -5
+
+    def arm(Q=one, K=one, B=1, nH=2, D=64, lay=L, mode=0, thr=0.9, hc=one, ws=one, wsb=1 << 20):
+        return lib.rf_arm_classify(Q, K, B, nH, D, C.byref(lay) if lay else None, None, mode, thr, hc, None, ws, wsb,
+                                   None)
+
+    assert arm(Q=None) == -1 and arm(hc=None) == -1
+    assert arm(D=32) == -2
+    assert arm(mode=2) == -4 and arm(thr=1.5) == -4 and arm(thr=float("nan")) == -4
+    assert arm(ws=None) == -6 and arm(wsb=8) == -6
+    assert rf.rf_arm_workspace_bytes(1, 2, L) == 1 * 2 * 2 * 64 * 4
+    assert rf.rf_arm_workspace_bytes(0, 2, L) == 0
+    needed = C.c_size_t(0)
+    assert lib.rf_plan_host(C.byref(L), None, 64, 7, None, None, 0, C.byref(needed)) == -4
+    assert lib.rf_plan_host(C.byref(L), None, 48, 0, None, None, 0, C.byref(needed)) == -5
+    small = (C.c_int32 * 2)()
+    assert lib.rf_plan_host(C.byref(L), None, 64, 0, None, small, 2, C.byref(needed)) == -6 and needed.value == 10
