@@ -114,7 +114,9 @@ __global__ void __launch_bounds__(64 * NW) attn_kernel(AttnArgs a) {
     load_q_frags<D>(Qh, qtok, hf, qf);
     int q_attr = 0, q_rad = 0x3fffffff;  // text queries keep everything
     if (listed) {
-        q_attr = attr[qtok];
+        // Spatial / Temporal compare the query's frame / position with the key's; the Textural
+        // table is 0 on kept keys and 1 on dropped ones, compared against 0 with radius 0
+        if (cls != RF_TEXTURAL) q_attr = attr[qtok];
         if (qtok < Nv) q_rad = pl.radius[cls];
     }
 
