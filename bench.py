@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the RainFusion hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic attention layer: ARM classifies
+every head from first-frame samples (Alg. 1), then the block-sparse attention runs with the
+classes the ARM left on the device (Eq. 1-5).  Inputs are resident in HBM before timing.
+Besides the timed steps the script measures, with events on the launch stream, the attention
+kernel alone (ARM-chosen classes, the one-third-per-pattern split, and the same kernel run
+dense for the speedup figure) and the ARM alone, and times the CPU oracle on a bounded
+sample of the same workload.  One JSON line is printed.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+
+
+def kept_pairs(cls, w, bw_s=0.25, bw_t=0.25, tau=2):
+    """Token pairs (query, key) one head keeps under a pattern: bookkeeping for FLOP counts."""
+    N, Nv, HW, T, tl = w.N, w.Nv, w.HW, w.T, w.text_len
+    if cls == 3:
+        return N * N
+
+    def band(n, r):
+        r = min(r, n - 1)
+        return n * (2 * r + 1) - r * (r + 1)
+
+    if cls == 0:
+        vv = band(T, math.floor(float(bw_s) * T)) * HW * HW
+    elif cls == 1:
+        vv = band(HW, math.floor(float(bw_t) * HW)) * T * T
+    else:
+        per_frame = sum(1 for y in range(w.H) for x in range(w.W) if (y - x) % tau == 0)
+        vv = Nv * per_frame * T
+    return vv + tl * N + Nv * tl  # text rows see everything, video rows see every text key
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="hunyuan720p")
+    ap.add_argument("--block", type=int, default=0, help="skip-list block (64|128); 0 = the workload's")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", default="", help="profiling aid: run just 'step', 'arm', 'thirds' or 'dense'")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
+
+    import torch
+
+    import paper_2505_21036_amd as rf
+    import rf_inputs as inp
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    w = inp.WORKLOADS[args.workload]
+    block = args.block or w.block
+    rl = rf.rf_layout(w.T, w.H, w.W, w.text_len)
+    Q, K, V = inp.full_qkv(w, dev)
+    O = torch.empty_like(Q)
+    hc = torch.empty(w.B, w.nH, dtype=torch.int32, device=dev)
+    rec = torch.empty(w.B, w.nH, 2, dtype=torch.float32, device=dev)
+    ws = torch.empty(max(rf.rf_arm_workspace_bytes(w.B, w.nH, rl), 4), dtype=torch.uint8, device=dev)
+    thirds = inp.thirds_classes(w).to(dev)
+    dense = torch.full((w.B, w.nH), rf.RF_DENSE, dtype=torch.int32, device=dev)
+
+    def arm():
+        rf.rf_arm_classify(Q, K, rl, None, rf.RF_SAMPLE_FIRST_FRAME, 0.9, hc, rec, ws)
+
+    def attn(classes):
+        rf.rf_sparse_attention(Q, K, V, classes, rl, None, block, O)
+
+    def step():
+        arm()
+        attn(hc)
+
+    def event_ms(fn, reps):
+        """Average duration of fn's launches, events recorded on the stream the kernels run on."""
+        pairs = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            pairs.append((a, b))
+        torch.cuda.synchronize()
+        return sum(a.elapsed_time(b) for a, b in pairs) / reps
+
+    if args.only:
+        fn = {"step": step, "arm": arm, "thirds": lambda: attn(thirds), "dense": lambda: attn(dense)}[args.only]
+        arm()
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        print(json.dumps({"only": args.only, "ms": (time.perf_counter() - t0) * 1e3 / args.steps}))
+        return
+
+    # ---- the timed region: K whole steps, attention launches bracketed by stream events
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        arm()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        attn(hc)
+        b.record()
+        ev.append((a, b))
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_attn_arm_classes = sum(a.elapsed_time(b) for a, b in ev) / args.steps
+    classes_host = hc.cpu().flatten().tolist()
+    recalls_host = rec.cpu().reshape(-1, 2).tolist()
+
+    reps = max(2, min(args.steps, 5))
+    ms_arm = event_ms(arm, reps)
+    attn(thirds)
+    ms_thirds = event_ms(lambda: attn(thirds), reps)
+    attn(dense)
+    ms_dense = event_ms(lambda: attn(dense), max(2, reps // 2))
+
+    # ---- FLOP bookkeeping: 4*D flops per (query, key) pair for QK^T and PV
+    per_pair = 4.0 * w.D
+    thirds_host = thirds.cpu().flatten().tolist()
+    useful_arm = per_pair * sum(kept_pairs(c, w) for c in classes_host)
+    useful_thirds = per_pair * sum(kept_pairs(c, w) for c in thirds_host)
+
+    def executed(classes):
+        tot = 0
+        for c in set(classes):
+            vis, _, _ = rf.plan_block_counts(rl, None, block, c)
+            tot += vis * classes.count(c)
+        return per_pair * block * block * tot
+
+    exec_arm, exec_thirds = executed(classes_host), executed(thirds_host)
+    dense_flops = w.dense_flops()
+    arm_flops = 2.0 * w.D * 2 * w.HW * w.HW * w.nH * w.B  # two passes of ~HW x HW scores per head
+
+    out = {
+        "metric": "sparse_attn_ms_per_layer",
+        "value": round(ms_step, 4),
+        "unit": "ms",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": "%s: B%d nH%d D%d, %d frames x %dx%d + %d text tokens = %d tokens, i.i.d. N(0,1)/sqrt(D) bf16; "
+                        "step = ARM (first-frame sampling, threshold 0.9) + block-sparse attention with the classes "
+                        "the ARM chose" % (w.name, w.B, w.nH, w.D, w.T, w.H, w.W, w.text_len, w.N),
+            "block": block,
+            "bandwidth": 0.25,
+            "tex_stride": 2,
+            "arm_classes": {"spatial": classes_host.count(0), "temporal": classes_host.count(1),
+                            "textural": classes_host.count(2)},
+        },
+        "roofline": {
+            "kernel": "attn_kernel<%d,%d> (ARM-chosen classes)" % (w.D, block // 32),
+            "bound": "mfma",
+            "achieved": round(useful_arm / ms_attn_arm_classes / 1e9, 2),
+            "peak": PEAK_BF16_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": round(useful_arm / ms_attn_arm_classes / 1e9 / PEAK_BF16_TFLOPS, 4),
+            "traffic": None,
+        },
+        "detail": {
+            "attention_ms_arm_classes": round(ms_attn_arm_classes, 4),
+            "attention_ms_thirds_split": round(ms_thirds, 4),
+            "attention_ms_dense_same_kernel": round(ms_dense, 4),
+            "speedup_vs_dense_arm_classes": round(ms_dense / ms_attn_arm_classes, 3),
+            "speedup_vs_dense_thirds_split": round(ms_dense / ms_thirds, 3),
+            "arm_ms": round(ms_arm, 4),
+            "arm_pct_of_sparse_attention": round(100.0 * ms_arm / ms_attn_arm_classes, 3),
+            "arm_tflops": round(arm_flops / ms_arm / 1e9, 2),
+            "tflops_useful_arm_classes": round(useful_arm / ms_attn_arm_classes / 1e9, 2),
+            "tflops_executed_arm_classes": round(exec_arm / ms_attn_arm_classes / 1e9, 2),
+            "tflops_useful_thirds": round(useful_thirds / ms_thirds / 1e9, 2),
+            "tflops_executed_thirds": round(exec_thirds / ms_thirds / 1e9, 2),
+            "tflops_dense": round(dense_flops / ms_dense / 1e9, 2),
+            "dense_equivalent_tflops_thirds": round(dense_flops / ms_thirds / 1e9, 2),
+            "kept_fraction_thirds": round(useful_thirds / dense_flops, 4),
+            "executed_fraction_thirds": round(exec_thirds / dense_flops, 4),
+            "mfma_frac_dense": round(dense_flops / ms_dense / 1e9 / PEAK_BF16_TFLOPS, 4),
+            "recalls_head0": [round(x, 4) for x in recalls_host[0]],
+            "paper_context": "paper reports 1.84-1.91x attention speedup (hardware not stated), ARM ~0.2 %",
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import numpy as np
+
+        import oracle as orc
+        ol = orc.Layout(w.T, w.H, w.W, w.text_len)
+        q, k, v = (t.float().numpy() for t in inp.head_qkv(w, 0, 0))
+        nthreads = orc.num_threads()
+        rows = np.array(inp.sample_rows(w, 64 * nthreads))
+        cls0 = classes_host[0]
+        orc.attention_rows(q, k, v, cls0, ol, orc.Params(), rows[:nthreads])  # warm the library / threads
+        t0 = time.perf_counter()
+        orc.attention_rows(q, k, v, cls0, ol, orc.Params(), rows)
+        t_rows = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        orc.arm_classify(q, k, ol, orc.Params(), orc.SAMPLE_FIRST_FRAME, 0.9)
+        t_arm = time.perf_counter() - t0
+        layer_ms = (t_rows / len(rows) * w.N + t_arm) * w.nH * w.B * 1e3
+        out["cpu_baseline"] = {
+            "value": round(layer_ms, 1),
+            "unit": "ms",
+            "cores": nthreads,
+            "kind": "oracle",
+            "sample": "fp64 oracle on head (0,0): %d complete query rows of class %d in %.2f s plus the full ARM of "
+                      "that head in %.2f s, scaled by N*nH*B/rows to one layer" % (len(rows), cls0, t_rows, t_arm),
+        }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
