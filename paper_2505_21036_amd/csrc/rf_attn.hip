@@ -18,7 +18,7 @@ struct VtTile {
     static constexpr int BYTES = D * ROW_BYTES;
     static constexpr int UNITS = (kTileK / 8) * (D / 4);  // a unit = 8 keys x 4 channels
     static constexpr int PER_THREAD = (UNITS + NT - 1) / NT;
-    uint2 reg[PER_THREAD][8];
+    u32x2 reg[PER_THREAD][8];
 
     template <typename F>
     __device__ __forceinline__ void fetch(const uint16_t* base, int tid, F row_token) {
@@ -29,7 +29,7 @@ struct VtTile {
                 const int kg = u / (D / 4), dc = u % (D / 4);
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    reg[i][e] = *reinterpret_cast<const uint2*>(base + static_cast<size_t>(row_token(8 * kg + e)) * D + 4 * dc);
+                    reg[i][e] = *reinterpret_cast<const u32x2*>(base + static_cast<size_t>(row_token(8 * kg + e)) * D + 4 * dc);
             }
         }
     }
@@ -39,24 +39,25 @@ struct VtTile {
             const int u = tid + i * NT;
             if (UNITS % NT == 0 || u < UNITS) {
                 const int kg = u / (D / 4), dc = u % (D / 4);
-                uint4 out[4];
+                uint32_t o[4][4];  // [channel][key pair]
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {  // keys 2w, 2w+1 side by side, one channel per output row
-                    const uint2 a = reg[i][2 * w], b = reg[i][2 * w + 1];
-                    (&out[0].x)[w] = __builtin_amdgcn_perm(b.x, a.x, 0x05040100u);
-                    (&out[1].x)[w] = __builtin_amdgcn_perm(b.x, a.x, 0x07060302u);
-                    (&out[2].x)[w] = __builtin_amdgcn_perm(b.y, a.y, 0x05040100u);
-                    (&out[3].x)[w] = __builtin_amdgcn_perm(b.y, a.y, 0x07060302u);
+                    const u32x2 a = reg[i][2 * w], b = reg[i][2 * w + 1];
+                    o[0][w] = __builtin_amdgcn_perm(b.x, a.x, 0x05040100u);
+                    o[1][w] = __builtin_amdgcn_perm(b.x, a.x, 0x07060302u);
+                    o[2][w] = __builtin_amdgcn_perm(b.y, a.y, 0x05040100u);
+                    o[3][w] = __builtin_amdgcn_perm(b.y, a.y, 0x07060302u);
                 }
 #pragma unroll
                 for (int dd = 0; dd < 4; ++dd)
-                    *reinterpret_cast<uint4*>(lds + (4 * dc + dd) * ROW_BYTES + 16 * kg) = out[dd];
+                    *reinterpret_cast<u32x4*>(lds + (4 * dc + dd) * ROW_BYTES + 16 * kg) =
+                        u32x4{o[dd][0], o[dd][1], o[dd][2], o[dd][3]};
             }
         }
     }
     // A operand of O^T = V^T P^T: channels 32*db + m, keys 16*u + 8*hf .. +7
     static __device__ __forceinline__ bf16x8 frag(const unsigned char* lds, int db, int u, int m, int hf) {
-        return as_bf16x8(*reinterpret_cast<const uint4*>(lds + (32 * db + m) * ROW_BYTES + 32 * u + 16 * hf));
+        return as_bf16x8(*reinterpret_cast<const u32x4*>(lds + (32 * db + m) * ROW_BYTES + 32 * u + 16 * hf));
     }
 };
 
@@ -68,62 +69,60 @@ struct AttnSmem {
     static constexpr int BYTES = A_OFF + 2 * kTileK * 4;
 };
 
-template <int D, int NW>
-__global__ void __launch_bounds__(64 * NW) attn_kernel(AttnArgs a) {
+// How a query block finds its key tiles.
+enum : int {
+    MODE_ALL = 0,      // every key block of the sequence in order (dense heads)
+    MODE_COMPACT = 1,  // every block of the compacted key sequence; rows go through the index table (Eq. 5)
+    MODE_LISTED = 2    // the CSR list of the head's pattern; partial blocks re-apply the predicate
+};
+
+struct QueryBlock {
+    int bh, qb, cls;
+    const int32_t* cols;  // MODE_LISTED: this query block's entries
+    int nblk;             // key blocks to visit
+    int keyN;             // length of the key sequence walked (N, or Nc when compacted)
+};
+
+// exp2 arguments may exceed 0 by at most this much before the running reference is moved: the
+// softmax is invariant to the reference, so a stale one only costs range, which fp32/bf16 have.
+constexpr float kRescaleSlack = 8.f;
+
+template <int D, int NW, int MODE>
+__device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, unsigned char* smem) {
     constexpr int NT = 64 * NW, BQ = 32 * NW, SUB = BQ / kTileK;
     using KT = KTile<D, NT>;
     using VT = VtTile<D, NT>;
     using SM = AttnSmem<D, NT>;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-
     const DevicePlan& pl = a.plan;
-    const int item = xcd_contiguous_item(blockIdx.x, pl.nQB * a.BH);
-    if (item < 0) return;
-    const int bh = item / pl.nQB, qb = item % pl.nQB;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, m = lane & 31;
-    const int N = pl.N, Nv = pl.Nv;
-
-    int cls = a.head_class[bh];
-    if (static_cast<unsigned>(cls) > 3u) cls = RF_DENSE;
-    // Textural query blocks made only of video tokens see the compacted key sequence (Eq. 5)
-    const bool compact = cls == RF_TEXTURAL && qb < pl.first_text_qb;
-    const bool listed = cls != RF_DENSE && !compact;
-    const int keyN = compact ? pl.Nc : N;
-    const int32_t* cols = nullptr;
-    int nblk;
-    if (listed) {
-        const int e0 = pl.row_ptr[cls][qb];
-        nblk = pl.row_ptr[cls][qb + 1] - e0;
-        cols = pl.cols[cls] + e0;
-    } else {
-        nblk = compact ? pl.nCB : pl.nKB;
-    }
-    const int ntiles = nblk * SUB;
+    const int N = pl.N, Nv = pl.Nv, keyN = qk.keyN;
+    const int ntiles = qk.nblk * SUB;
     const int32_t* cidx = pl.cidx;
-    const int32_t* attr = listed ? pl.attr[cls] : nullptr;
+    const int32_t* attr = MODE == MODE_LISTED ? pl.attr[qk.cls] : nullptr;
 
-    const size_t head_off = static_cast<size_t>(bh) * N * D;
+    const size_t head_off = static_cast<size_t>(qk.bh) * N * D;
     const uint16_t* Qh = a.Q + head_off;
     const uint16_t* Kh = a.K + head_off;
     const uint16_t* Vh = a.V + head_off;
 
     // this lane's query
-    const int qrow = qb * BQ + wave * 32 + m;
+    const int qrow = qk.qb * BQ + wave * 32 + m;
     const int qtok = min(qrow, N - 1);
     bf16x8 qf[D / 16];
     load_q_frags<D>(Qh, qtok, hf, qf);
     int q_attr = 0, q_rad = 0x3fffffff;  // text queries keep everything
-    if (listed) {
+    if (MODE == MODE_LISTED) {
         // Spatial / Temporal compare the query's frame / position with the key's; the Textural
         // table is 0 on kept keys and 1 on dropped ones, compared against 0 with radius 0
-        if (cls != RF_TEXTURAL) q_attr = attr[qtok];
-        if (qtok < Nv) q_rad = pl.radius[cls];
+        if (qk.cls != RF_TEXTURAL) q_attr = attr[qtok];
+        if (qtok < Nv) q_rad = pl.radius[qk.cls];
     }
 
     f32x16 oacc[D / 32];
 #pragma unroll
     for (int db = 0; db < D / 32; ++db) oacc[db] = f32x16{0};
-    float m_run = -INFINITY, l_run = 0.f;
+    // m_ref: reference subtracted inside exp2 (in units of raw score); l_run: this lane's share of the denominator
+    float m_ref = -INFINITY, l_run = 0.f;
     const float c = a.scale_log2;
 
     KT kt;
@@ -134,7 +133,7 @@ __global__ void __launch_bounds__(64 * NW) attn_kernel(AttnArgs a) {
     auto tile_info = [&](int t, int* k0, bool* partial) {
         const int blk = t / SUB, s = t % SUB;
         int entry;
-        if (listed) entry = cols[blk];
+        if (MODE == MODE_LISTED) entry = qk.cols[blk];
         else entry = blk | ((blk + 1) * BQ > keyN ? RF_PLAN_PARTIAL : 0);
         *k0 = (entry & ~RF_PLAN_PARTIAL) * BQ + s * kTileK;
         *partial = (entry & RF_PLAN_PARTIAL) != 0;
@@ -145,17 +144,17 @@ __global__ void __launch_bounds__(64 * NW) attn_kernel(AttnArgs a) {
         tile_info(t, &k0, &partial);
         auto row_token = [&](int r) {
             const int key = min(k0 + r, keyN - 1);
-            return compact ? cidx[key] : key;
+            return MODE == MODE_COMPACT ? cidx[key] : key;
         };
         kt.fetch(Kh, tid, row_token);
         vt.fetch(Vh, tid, row_token);
-        if (listed && partial && tid < kTileK) attr_reg = attr[min(k0 + tid, N - 1)];
+        if (MODE == MODE_LISTED && partial && tid < kTileK) attr_reg = attr[min(k0 + tid, N - 1)];
     };
     auto stash_tile = [&](int t) {
         const int buf = t & 1;
         kt.stash(smem + SM::K_OFF + buf * KT::BYTES, tid);
         vt.stash(smem + SM::V_OFF + buf * VT::BYTES, tid);
-        if (tid < kTileK) reinterpret_cast<int*>(smem + SM::A_OFF)[buf * kTileK + tid] = attr_reg;
+        if (MODE == MODE_LISTED && tid < kTileK) reinterpret_cast<int*>(smem + SM::A_OFF)[buf * kTileK + tid] = attr_reg;
     };
 
     if (ntiles > 0) {
@@ -186,7 +185,7 @@ __global__ void __launch_bounds__(64 * NW) attn_kernel(AttnArgs a) {
                     const int koff = 32 * kb2 + key_of_reg(r, hf);
                     const int kidx = k0 + koff;
                     bool ok = kidx < keyN;
-                    if (listed) {
+                    if (MODE == MODE_LISTED) {
                         const int d = q_attr - al[koff];
                         ok = ok && ((d < 0 ? -d : d) <= q_rad || kidx >= Nv);
                     }
@@ -201,10 +200,20 @@ __global__ void __launch_bounds__(64 * NW) attn_kernel(AttnArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) mt = fmaxf(mt, s[kb2][r]);
         mt = fmaxf(mt, other_half(mt));
-        const float m_new = fmaxf(m_run, mt);
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = fast_exp2((m_run - m_use) * c);
-        const float mc = m_use * c;
+        // move the reference only when some row of this wavefront outgrew it by more than the slack
+        const bool grow = (mt - m_ref) * c > kRescaleSlack || (m_ref == -INFINITY && mt > -INFINITY);
+        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+            const float m_new = fmaxf(m_ref, mt);
+            const float m_use = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = fast_exp2((m_ref - m_use) * c);
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+            m_ref = m_new;
+        }
+        const float mc = (m_ref == -INFINITY ? 0.f : m_ref) * c;
         float psum = 0.f;
         bf16x8 pf[4];
 #pragma unroll
@@ -217,7 +226,7 @@ __global__ void __launch_bounds__(64 * NW) attn_kernel(AttnArgs a) {
             }
 #pragma unroll
             for (int u2 = 0; u2 < 2; ++u2) {
-                uint4 w;
+                u32x4 w;
                 w.x = pack_bf16(p[8 * u2 + 0], p[8 * u2 + 1]);
                 w.y = pack_bf16(p[8 * u2 + 2], p[8 * u2 + 3]);
                 w.z = pack_bf16(p[8 * u2 + 4], p[8 * u2 + 5]);
@@ -225,19 +234,13 @@ __global__ void __launch_bounds__(64 * NW) attn_kernel(AttnArgs a) {
                 pf[2 * kb2 + u2] = as_bf16x8(w);
             }
         }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
+        l_run += psum;
 
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db) {
-            f32x16 acc = oacc[db];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] *= alpha;
+        for (int db = 0; db < D / 32; ++db)
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(VT::frag(vl, db, u, m, hf), pf[u], acc, 0, 0, 0);
-            oacc[db] = acc;
-        }
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(VT::frag(vl, db, u, m, hf), pf[u], oacc[db], 0, 0, 0);
 
         if (t + 1 < ntiles) stash_tile(t + 1);
         __syncthreads();
@@ -253,11 +256,42 @@ __global__ void __launch_bounds__(64 * NW) attn_kernel(AttnArgs a) {
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
-                uint2 w;
+                u32x2 w;
                 w.x = pack_bf16(oacc[db][4 * rq + 0] * inv, oacc[db][4 * rq + 1] * inv);
                 w.y = pack_bf16(oacc[db][4 * rq + 2] * inv, oacc[db][4 * rq + 3] * inv);
-                *reinterpret_cast<uint2*>(orow + 32 * db + 8 * rq + 4 * hf) = w;
+                *reinterpret_cast<u32x2*>(orow + 32 * db + 8 * rq + 4 * hf) = w;
             }
+    }
+}
+
+template <int D, int NW>
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) attn_kernel(AttnArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const DevicePlan& pl = a.plan;
+    const int item = xcd_contiguous_item(blockIdx.x, pl.nQB * a.BH);
+    if (item < 0) return;
+    QueryBlock qk;
+    qk.bh = item / pl.nQB;
+    qk.qb = item % pl.nQB;
+    int cls = a.head_class[qk.bh];
+    if (static_cast<unsigned>(cls) > 3u) cls = RF_DENSE;
+    qk.cls = cls;
+    qk.cols = nullptr;
+    if (cls == RF_DENSE) {
+        qk.nblk = pl.nKB;
+        qk.keyN = pl.N;
+        attend<D, NW, MODE_ALL>(a, qk, smem);
+    } else if (cls == RF_TEXTURAL && qk.qb < pl.first_text_qb) {
+        // Textural query blocks made only of video tokens see the compacted key sequence
+        qk.nblk = pl.nCB;
+        qk.keyN = pl.Nc;
+        attend<D, NW, MODE_COMPACT>(a, qk, smem);
+    } else {
+        const int e0 = pl.row_ptr[cls][qk.qb];
+        qk.nblk = pl.row_ptr[cls][qk.qb + 1] - e0;
+        qk.cols = pl.cols[cls] + e0;
+        qk.keyN = pl.N;
+        attend<D, NW, MODE_LISTED>(a, qk, smem);
     }
 }
 

@@ -17,6 +17,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 // MFMA result register r of lane half hf holds matrix row 8*(r/4) + 4*hf + r%4.  Letting the
 // lane that feeds matrix row m read key  swap_bits23(m)  makes register r of half hf hold key
@@ -27,7 +29,7 @@ __device__ __forceinline__ int key_of_mfma_row(int m) {
 }
 __device__ __forceinline__ int key_of_reg(int r, int hf) { return 16 * (r >> 3) + 8 * hf + (r & 7); }
 
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     f32x2 v = {lo, hi};
@@ -54,7 +56,7 @@ struct KTile {
     static constexpr int BYTES = kTileK * ROW_BYTES;
     static constexpr int CHUNKS = kTileK * D / 8;  // 16-byte pieces
     static constexpr int PER_THREAD = (CHUNKS + NT - 1) / NT;
-    uint4 reg[PER_THREAD];
+    u32x4 reg[PER_THREAD];
 
     // row_token(r) gives the token whose K row goes to tile row r (already clamped in range)
     template <typename F>
@@ -64,7 +66,7 @@ struct KTile {
             const int c = tid + i * NT;
             if (CHUNKS % NT == 0 || c < CHUNKS) {
                 const int row = c / (D / 8), col = c % (D / 8);
-                reg[i] = *reinterpret_cast<const uint4*>(base + static_cast<size_t>(row_token(row)) * D + col * 8);
+                reg[i] = *reinterpret_cast<const u32x4*>(base + static_cast<size_t>(row_token(row)) * D + col * 8);
             }
         }
     }
@@ -74,14 +76,14 @@ struct KTile {
             const int c = tid + i * NT;
             if (CHUNKS % NT == 0 || c < CHUNKS) {
                 const int row = c / (D / 8), col = c % (D / 8);
-                *reinterpret_cast<uint4*>(lds + row * ROW_BYTES + col * 16) = reg[i];
+                *reinterpret_cast<u32x4*>(lds + row * ROW_BYTES + col * 16) = reg[i];
             }
         }
     }
     // A operand of S^T = K Q^T: keys 32*kb2 .. +31 (permuted per lane), channels 16*c + 8*hf .. +7
     static __device__ __forceinline__ bf16x8 frag(const unsigned char* lds, int kb2, int c, int m, int hf) {
         const int row = 32 * kb2 + key_of_mfma_row(m);
-        return as_bf16x8(*reinterpret_cast<const uint4*>(lds + row * ROW_BYTES + 32 * c + 16 * hf));
+        return as_bf16x8(*reinterpret_cast<const u32x4*>(lds + row * ROW_BYTES + 32 * c + 16 * hf));
     }
 };
 
@@ -90,7 +92,7 @@ template <int D>
 __device__ __forceinline__ void load_q_frags(const uint16_t* base, int token, int hf, bf16x8 (&qf)[D / 16]) {
 #pragma unroll
     for (int c = 0; c < D / 16; ++c)
-        qf[c] = as_bf16x8(*reinterpret_cast<const uint4*>(base + static_cast<size_t>(token) * D + 16 * c + 8 * hf));
+        qf[c] = as_bf16x8(*reinterpret_cast<const u32x4*>(base + static_cast<size_t>(token) * D + 16 * c + 8 * hf));
 }
 
 // S^T tile (64 keys x 32 queries per wavefront) = two 32x32 MFMA blocks.
