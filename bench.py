@@ -145,7 +145,7 @@ def main():
         for c in set(classes):
             vis, _, _ = rf.plan_block_counts(rl, None, block, c)
             tot += vis * classes.count(c)
-        return per_pair * block * block * tot
+        return per_pair * block * rf.RF_KEY_TILE * tot
 
     exec_arm, exec_thirds = executed(classes_host), executed(thirds_host)
     dense_flops = w.dense_flops()

@@ -87,8 +87,8 @@ size_t rf_arm_workspace_bytes(int B, int nH, const rf_layout *layout, const rf_p
 /*
  * Sparse attention forward, Eq. 1-2 with the mask of each head's pattern (Eq. 3-5):
  *   O[b,h,i,:] = sum_j softmax_j(q_i . k_j / sqrt(D) over kept j) * v_j.
- * The mask is token-level; `block` (64 or 128) only sets the granularity at which whole
- * (query block, key block) pairs with no kept token pair are skipped, so O does not
+ * The mask is token-level; `block` (64 or 128) is the number of query rows per block, and
+ * (query block, 64-key tile) pairs with no kept token pair are skipped, so O does not
  * depend on it.  Scores and sums are accumulated in fp32, O is rounded to bf16.
  * Q, K, V     : device, bf16 [B, nH, N, D].
  * head_class  : device, int32 [B*nH], values of rf_head_class; read on the device, so the
@@ -101,18 +101,20 @@ int rf_sparse_attention(const void *Q, const void *K, const void *V, const int32
                         void *O, void *stream);
 
 /*
- * Host-side view of the block list rf_sparse_attention walks (Fig. 2a "applying the sparse
- * pattern"): for pattern `cls`, which key blocks each query block visits.  Pure host code,
- * no GPU needed.
+ * Host-side view of the list rf_sparse_attention walks (Fig. 2a "applying the sparse
+ * pattern"): for pattern `cls`, which key tiles each query block visits.  Query blocks are
+ * `block` rows; key tiles are always RF_KEY_TILE = 64 keys, so a list is never coarser than
+ * a block x block tiling would be.  Pure host code, no GPU needed.
  *   row_ptr : host, int32 [nQB + 1] (nQB = ceil(N / block)), written; may be NULL to only size.
- *   cols    : host, int32 [cap]; entry = key-block index, plus RF_PLAN_PARTIAL if the pair
+ *   cols    : host, int32 [cap]; entry = key-tile index, plus RF_PLAN_PARTIAL if the pair
  *             contains a dropped token pair or runs past the last token (the kernel applies the
  *             token predicate there).  For RF_TEXTURAL, query blocks made only of video tokens
- *             index blocks of the COMPACTED key sequence (kept keys in token order, then text).
+ *             index tiles of the COMPACTED key sequence (kept keys in token order, then text).
  *   needed  : host, receives the number of entries.
- * Returns RF_ERR_WORKSPACE if cap < *needed (nothing but *needed is written then).
+ * Returns RF_ERR_WORKSPACE if cap < *needed (nothing but *needed and row_ptr is written then).
  */
 #define RF_PLAN_PARTIAL 0x40000000
+#define RF_KEY_TILE 64
 int rf_plan_host(const rf_layout *layout, const rf_params *params, int block, int cls,
                  int32_t *row_ptr, int32_t *cols, size_t cap, size_t *needed);
 

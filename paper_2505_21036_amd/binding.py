@@ -13,6 +13,7 @@ import numpy as np
 RF_SPATIAL, RF_TEMPORAL, RF_TEXTURAL, RF_DENSE = 0, 1, 2, 3
 RF_SAMPLE_FIRST_FRAME, RF_SAMPLE_EQUAL_INTERVAL = 0, 1
 RF_PLAN_PARTIAL = 0x40000000
+RF_KEY_TILE = 64
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "librainfusion.so")
@@ -167,10 +168,12 @@ def rf_plan_host(layout, params, block, cls):
 
 
 def plan_block_counts(layout, params, block, cls):
-    """(visited block pairs, of which partial, all block pairs) for one class: bookkeeping for FLOP counts."""
+    """(visited (query block, key tile) pairs, of which partial, all such pairs) for one class:
+    bookkeeping for FLOP counts; a pair stands for block x RF_KEY_TILE scores."""
     row_ptr, cols = rf_plan_host(layout, params, block, cls)
-    nqb = len(row_ptr) - 1
-    return int(len(cols)), int((cols & RF_PLAN_PARTIAL != 0).sum()), nqb * nqb
+    N = layout.T * layout.H * layout.W + layout.text_len
+    nqb, nkt = len(row_ptr) - 1, (N + RF_KEY_TILE - 1) // RF_KEY_TILE
+    return int(len(cols)), int((cols & RF_PLAN_PARTIAL != 0).sum()), nqb * nkt
 
 
 def rf_plan_clear():

@@ -93,7 +93,7 @@ int get_attention_plan(const Geometry& g, int block, const DevicePlan** out) {
         d.radius[RF_TEMPORAL] = g.r_temporal;
         d.radius[RF_TEXTURAL] = 0;
         d.N = g.N; d.Nv = g.Nv; d.Nc = hp.Nc;
-        d.block = block; d.nQB = hp.nQB; d.nKB = hp.nKB; d.nCB = hp.nCB;
+        d.block = block; d.nQB = hp.nQB; d.nKT = hp.nKT; d.nCT = hp.nCT;
         d.first_text_qb = hp.first_text_qb;
         cp = p.get();
         g_plans.push_back(std::move(p));

@@ -1,85 +1,128 @@
 // Block-sparse attention forward for RainFusion's head patterns (Eq. 1-5; Fig. 2a), gfx950.
 //
-// One workgroup = one query block of one head.  It reads the head's class on the device,
-// walks that class's list of key blocks (skipped blocks cost no traffic), stages K and V^T
-// tiles of 64 keys through LDS with one tile of prefetch held in registers, forms the
-// transposed score tile with bf16 MFMA, runs the online softmax in fp32 with exp2, and
-// accumulates O^T = V^T P^T with bf16 MFMA.  In key blocks flagged partial the token-level
-// predicate of the pattern is re-applied to each score.
+// One workgroup = one query block (64 or 128 rows) of one head.  It reads the head's class on
+// the device, walks that class's list of 64-key tiles (skipped tiles cost no traffic), stages K
+// and V^T tiles through LDS with one tile of prefetch held in registers, forms the transposed
+// score tile with bf16 MFMA, runs the online softmax in fp32 with exp2, and accumulates
+// O^T = V^T P^T with bf16 MFMA.  In tiles flagged partial the token-level predicate of the
+// pattern is re-applied to each score.
 #include "rf_device.h"
 
 namespace rf {
 
-// V tile stored transposed in LDS: one row per channel holding the tile's 64 keys, so the
-// A operand of O^T = V^T P^T (8 consecutive keys of one channel) is a single 16-byte read.
-template <int D, int NT>
-struct VtTile {
-    static constexpr int ROW_BYTES = 2 * kTileK + 16;
-    static constexpr int BYTES = D * ROW_BYTES;
-    static constexpr int UNITS = (kTileK / 8) * (D / 4);  // a unit = 8 keys x 4 channels
-    static constexpr int PER_THREAD = (UNITS + NT - 1) / NT;
-    u32x2 reg[PER_THREAD][8];
+// How a query block finds its key tiles.
+enum : int {
+    MODE_ALL = 0,      // every key tile of the sequence in order (dense heads)
+    MODE_COMPACT = 1,  // every tile of the compacted key sequence; rows go through the index table (Eq. 5)
+    MODE_LISTED = 2    // the CSR list of the head's pattern; partial tiles re-apply the predicate
+};
 
-    template <typename F>
-    __device__ __forceinline__ void fetch(const uint16_t* base, int tid, F row_token) {
+// Global -> register -> LDS staging of one 64-key tile of K (row-major, padded rows) and of V
+// (transposed: one LDS row per channel, so the A operand of O^T = V^T P^T, eight consecutive
+// keys of one channel, is a single 16-byte read).
+//
+// A thread owns "units": unit (kg, dc) covers keys 8*kg .. 8*kg+7.  From V it loads channels
+// 4*dc .. 4*dc+3 of those 8 rows (8 bytes each) and transposes them in registers; from K it
+// loads 4 of the same 8 rows, 16 bytes each.  All row addresses of a unit therefore derive
+// from the same 8 tokens.
+template <int D, int NT>
+struct Stager {
+    static constexpr int K_ROW = 2 * D + 16;       // bytes; +16 pad: conflict-free 16-B reads down a column
+    static constexpr int V_ROW = 2 * kTileK + 16;  // bytes
+    static constexpr int K_BYTES = kTileK * K_ROW;
+    static constexpr int V_BYTES = D * V_ROW;
+    static constexpr int DC = D / 4;               // units per key group
+    static constexpr int UNITS = (kTileK / 8) * DC;
+    static constexpr int PER_THREAD = (UNITS + NT - 1) / NT;
+    static constexpr bool EXACT = UNITS % NT == 0;
+
+    u32x4 kreg[PER_THREAD][4];
+    u32x2 vreg[PER_THREAD][8];
+
+    static __device__ __forceinline__ int k_row_in_group(int dc) { return 4 * (dc / (D / 8)); }
+    static __device__ __forceinline__ int k_chunk(int dc) { return dc % (D / 8); }
+
+    // vtok(i, e): token of key 8*kg + e of this thread's unit i (e = 0..7); ktok(i, j): token of
+    // the j-th K row of the unit (key 8*kg + k_row_in_group(dc) + j, j = 0..3).  Offsets are
+    // 32-bit byte offsets from the base pointers (a head is < 4 GiB).
+    template <typename FV, typename FK>
+    __device__ __forceinline__ void fetch(const unsigned char* kbase, const unsigned char* vbase, int tid, FV vtok,
+                                          FK ktok) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             const int u = tid + i * NT;
-            if (UNITS % NT == 0 || u < UNITS) {
-                const int kg = u / (D / 4), dc = u % (D / 4);
+            if (EXACT || u < UNITS) {
+                const int dc = u % DC;
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    reg[i][e] = *reinterpret_cast<const u32x2*>(base + static_cast<size_t>(row_token(8 * kg + e)) * D + 4 * dc);
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t row_off = static_cast<uint32_t>(vtok(i, e)) * (2u * D);
+                    vreg[i][e] = *reinterpret_cast<const u32x2*>(vbase + row_off + 8u * dc);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t row_off = static_cast<uint32_t>(ktok(i, j)) * (2u * D);
+                    kreg[i][j] = *reinterpret_cast<const u32x4*>(kbase + row_off + 16u * k_chunk(dc));
+                }
             }
         }
     }
-    __device__ __forceinline__ void stash(unsigned char* lds, int tid) const {
+
+    __device__ __forceinline__ void stash(unsigned char* kl, unsigned char* vl, int tid) const {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             const int u = tid + i * NT;
-            if (UNITS % NT == 0 || u < UNITS) {
-                const int kg = u / (D / 4), dc = u % (D / 4);
+            if (EXACT || u < UNITS) {
+                const int kg = u / DC, dc = u % DC;
+                const int r0 = 8 * kg + k_row_in_group(dc);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    *reinterpret_cast<u32x4*>(kl + (r0 + j) * K_ROW + 16 * k_chunk(dc)) = kreg[i][j];
                 uint32_t o[4][4];  // [channel][key pair]
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {  // keys 2w, 2w+1 side by side, one channel per output row
-                    const u32x2 a = reg[i][2 * w], b = reg[i][2 * w + 1];
+                    const u32x2 a = vreg[i][2 * w], b = vreg[i][2 * w + 1];
                     o[0][w] = __builtin_amdgcn_perm(b.x, a.x, 0x05040100u);
                     o[1][w] = __builtin_amdgcn_perm(b.x, a.x, 0x07060302u);
                     o[2][w] = __builtin_amdgcn_perm(b.y, a.y, 0x05040100u);
                     o[3][w] = __builtin_amdgcn_perm(b.y, a.y, 0x07060302u);
                 }
+                // 16-byte key chunk kg of channel row d sits at chunk position kg ^ ((d >> 4) & 3):
+                // with the 36-dword row pitch this spreads the 16 lanes of a write phase over all banks
+                const int pos = kg ^ ((dc >> 2) & 3);
 #pragma unroll
                 for (int dd = 0; dd < 4; ++dd)
-                    *reinterpret_cast<u32x4*>(lds + (4 * dc + dd) * ROW_BYTES + 16 * kg) =
+                    *reinterpret_cast<u32x4*>(vl + (4 * dc + dd) * V_ROW + 16 * pos) =
                         u32x4{o[dd][0], o[dd][1], o[dd][2], o[dd][3]};
             }
         }
     }
+
+    // A operand of S^T = K Q^T: keys 32*kb2 .. +31 (permuted per lane), channels 16*c + 8*hf .. +7
+    static __device__ __forceinline__ bf16x8 k_frag(const unsigned char* kl, int kb2, int c, int m, int hf) {
+        const int row = 32 * kb2 + key_of_mfma_row(m);
+        return as_bf16x8(*reinterpret_cast<const u32x4*>(kl + row * K_ROW + 32 * c + 16 * hf));
+    }
     // A operand of O^T = V^T P^T: channels 32*db + m, keys 16*u + 8*hf .. +7
-    static __device__ __forceinline__ bf16x8 frag(const unsigned char* lds, int db, int u, int m, int hf) {
-        return as_bf16x8(*reinterpret_cast<const u32x4*>(lds + (32 * db + m) * ROW_BYTES + 32 * u + 16 * hf));
+    static __device__ __forceinline__ bf16x8 v_frag(const unsigned char* vl, int db, int u, int m, int hf) {
+        const int row = 32 * db + m;
+        const int pos = (2 * u + hf) ^ ((row >> 4) & 3);
+        return as_bf16x8(*reinterpret_cast<const u32x4*>(vl + row * V_ROW + 16 * pos));
     }
 };
 
 template <int D, int NT>
 struct AttnSmem {
+    using ST = Stager<D, NT>;
     static constexpr int K_OFF = 0;
-    static constexpr int V_OFF = 2 * KTile<D, NT>::BYTES;
-    static constexpr int A_OFF = V_OFF + 2 * VtTile<D, NT>::BYTES;
-    static constexpr int BYTES = A_OFF + 2 * kTileK * 4;
-};
-
-// How a query block finds its key tiles.
-enum : int {
-    MODE_ALL = 0,      // every key block of the sequence in order (dense heads)
-    MODE_COMPACT = 1,  // every block of the compacted key sequence; rows go through the index table (Eq. 5)
-    MODE_LISTED = 2    // the CSR list of the head's pattern; partial blocks re-apply the predicate
+    static constexpr int V_OFF = 2 * ST::K_BYTES;
+    static constexpr int SIDE_OFF = V_OFF + 2 * ST::V_BYTES;  // ring of 3 x 64 ints: key indices or key attributes
+    static constexpr int BYTES = SIDE_OFF + 3 * kTileK * 4;
 };
 
 struct QueryBlock {
     int bh, qb, cls;
-    const int32_t* cols;  // MODE_LISTED: this query block's entries
-    int nblk;             // key blocks to visit
+    const int32_t* cols;  // MODE_LISTED: this query block's tile entries
+    int ntiles;           // key tiles to visit
     int keyN;             // length of the key sequence walked (N, or Nc when compacted)
 };
 
@@ -89,21 +132,21 @@ constexpr float kRescaleSlack = 8.f;
 
 template <int D, int NW, int MODE>
 __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, unsigned char* smem) {
-    constexpr int NT = 64 * NW, BQ = 32 * NW, SUB = BQ / kTileK;
-    using KT = KTile<D, NT>;
-    using VT = VtTile<D, NT>;
+    constexpr int NT = 64 * NW, BQ = 32 * NW;
+    using ST = Stager<D, NT>;
     using SM = AttnSmem<D, NT>;
     const DevicePlan& pl = a.plan;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, m = lane & 31;
-    const int N = pl.N, Nv = pl.Nv, keyN = qk.keyN;
-    const int ntiles = qk.nblk * SUB;
-    const int32_t* cidx = pl.cidx;
-    const int32_t* attr = MODE == MODE_LISTED ? pl.attr[qk.cls] : nullptr;
+    const int N = pl.N, Nv = pl.Nv, keyN = qk.keyN, ntiles = qk.ntiles;
+    // per-key side data staged through LDS two tiles ahead: the token index of each key of the
+    // compacted sequence, or the pattern attribute (frame / position / kept flag) of each key
+    const int32_t* side_src = MODE == MODE_COMPACT ? pl.cidx : (MODE == MODE_LISTED ? pl.attr[qk.cls] : nullptr);
+    int* side = reinterpret_cast<int*>(smem + SM::SIDE_OFF);
 
-    const size_t head_off = static_cast<size_t>(qk.bh) * N * D;
-    const uint16_t* Qh = a.Q + head_off;
-    const uint16_t* Kh = a.K + head_off;
-    const uint16_t* Vh = a.V + head_off;
+    const size_t head_bytes = static_cast<size_t>(qk.bh) * N * D * 2;
+    const unsigned char* Kh = reinterpret_cast<const unsigned char*>(a.K) + head_bytes;
+    const unsigned char* Vh = reinterpret_cast<const unsigned char*>(a.V) + head_bytes;
+    const uint16_t* Qh = a.Q + static_cast<size_t>(qk.bh) * N * D;
 
     // this lane's query
     const int qrow = qk.qb * BQ + wave * 32 + m;
@@ -114,9 +157,10 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
     if (MODE == MODE_LISTED) {
         // Spatial / Temporal compare the query's frame / position with the key's; the Textural
         // table is 0 on kept keys and 1 on dropped ones, compared against 0 with radius 0
-        if (qk.cls != RF_TEXTURAL) q_attr = attr[qtok];
+        if (qk.cls != RF_TEXTURAL) q_attr = side_src[qtok];
         if (qtok < Nv) q_rad = pl.radius[qk.cls];
     }
+    const uint32_t q_lo = static_cast<uint32_t>(q_rad - q_attr), q_span = 2u * static_cast<uint32_t>(q_rad);
 
     f32x16 oacc[D / 32];
 #pragma unroll
@@ -125,72 +169,111 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
     float m_ref = -INFINITY, l_run = 0.f;
     const float c = a.scale_log2;
 
-    KT kt;
-    VT vt;
-    int attr_reg = 0;
+    ST st;
+    int side_reg = 0;
 
-    // tile t -> (first key position, partial flag)
-    auto tile_info = [&](int t, int* k0, bool* partial) {
-        const int blk = t / SUB, s = t % SUB;
-        int entry;
-        if (MODE == MODE_LISTED) entry = qk.cols[blk];
-        else entry = blk | ((blk + 1) * BQ > keyN ? RF_PLAN_PARTIAL : 0);
-        *k0 = (entry & ~RF_PLAN_PARTIAL) * BQ + s * kTileK;
-        *partial = (entry & RF_PLAN_PARTIAL) != 0;
+    auto entry_of = [&](int t) -> int {
+        if (MODE == MODE_LISTED) return qk.cols[t];
+        return t | ((t + 1) * kTileK > keyN ? (RF_PLAN_PARTIAL | kTileBoundary) : 0);
     };
-    auto fetch_tile = [&](int t) {
-        int k0;
-        bool partial;
-        tile_info(t, &k0, &partial);
-        auto row_token = [&](int r) {
-            const int key = min(k0 + r, keyN - 1);
-            return MODE == MODE_COMPACT ? cidx[key] : key;
-        };
-        kt.fetch(Kh, tid, row_token);
-        vt.fetch(Vh, tid, row_token);
-        if (MODE == MODE_LISTED && partial && tid < kTileK) attr_reg = attr[min(k0 + tid, N - 1)];
+    auto load_side = [&](int entry) {
+        if (MODE == MODE_ALL) return;
+        const int k0 = (entry & kTileIndexMask) * kTileK;
+        if (tid < kTileK) side_reg = side_src[min(k0 + tid, keyN - 1)];
+    };
+    auto stash_side = [&](int t) {
+        if (MODE == MODE_ALL) return;
+        if (tid < kTileK) side[(t % 3) * kTileK + tid] = side_reg;
+    };
+    // first key of unit i's key group inside the tile, and first K row of the unit inside the group
+    auto group_key = [&](int i) { return 8 * (((tid + i * NT) / ST::DC) & 7); };
+    auto k_first = [&](int i) { return ST::k_row_in_group((tid + i * NT) % ST::DC); };
+    auto fetch_tile = [&](int t, int entry) {
+        const int k0 = (entry & kTileIndexMask) * kTileK;
+        if (MODE == MODE_COMPACT) {
+            const int* idx = side + (t % 3) * kTileK;
+            st.fetch(Kh, Vh, tid, [&](int i, int e) { return idx[group_key(i) + e]; },
+                     [&](int i, int j) { return idx[group_key(i) + k_first(i) + j]; });
+        } else if (k0 + kTileK <= keyN) {
+            // full tile: rows are consecutive tokens, everything but the tile origin is loop invariant
+            const unsigned char* kb = Kh + static_cast<size_t>(k0) * (2 * D);
+            const unsigned char* vb = Vh + static_cast<size_t>(k0) * (2 * D);
+            st.fetch(kb, vb, tid, [&](int i, int e) { return group_key(i) + e; },
+                     [&](int i, int j) { return group_key(i) + k_first(i) + j; });
+        } else {
+            st.fetch(Kh, Vh, tid, [&](int i, int e) { return min(k0 + group_key(i) + e, keyN - 1); },
+                     [&](int i, int j) { return min(k0 + group_key(i) + k_first(i) + j, keyN - 1); });
+        }
     };
     auto stash_tile = [&](int t) {
-        const int buf = t & 1;
-        kt.stash(smem + SM::K_OFF + buf * KT::BYTES, tid);
-        vt.stash(smem + SM::V_OFF + buf * VT::BYTES, tid);
-        if (MODE == MODE_LISTED && tid < kTileK) reinterpret_cast<int*>(smem + SM::A_OFF)[buf * kTileK + tid] = attr_reg;
+        st.stash(smem + SM::K_OFF + (t & 1) * ST::K_BYTES, smem + SM::V_OFF + (t & 1) * ST::V_BYTES, tid);
     };
 
+    // software pipeline: side data runs two tiles ahead of the compute, K/V one tile ahead
+    int e_cur = 0, e_nxt = 0, e_nx2 = 0;
     if (ntiles > 0) {
-        fetch_tile(0);
+        e_cur = entry_of(0);
+        if (ntiles > 1) e_nxt = entry_of(1);
+        load_side(e_cur);
+        stash_side(0);
+        if (ntiles > 1) {
+            load_side(e_nxt);
+            stash_side(1);
+        }
+    }
+    __syncthreads();
+    if (ntiles > 0) {
+        fetch_tile(0, e_cur);
         stash_tile(0);
     }
     __syncthreads();
 
     for (int t = 0; t < ntiles; ++t) {
         const int buf = t & 1;
-        if (t + 1 < ntiles) fetch_tile(t + 1);
+        if (t + 2 < ntiles) e_nx2 = entry_of(t + 2);
+        if (t + 1 < ntiles) fetch_tile(t + 1, e_nxt);
+        if (t + 2 < ntiles) load_side(e_nx2);
 
-        int k0;
-        bool partial;
-        tile_info(t, &k0, &partial);
-        const unsigned char* kl = smem + SM::K_OFF + buf * KT::BYTES;
-        const unsigned char* vl = smem + SM::V_OFF + buf * VT::BYTES;
+        const unsigned char* kl = smem + SM::K_OFF + buf * ST::K_BYTES;
+        const unsigned char* vl = smem + SM::V_OFF + buf * ST::V_BYTES;
 
         f32x16 s[2];
-        score_tile<D, NT>(kl, qf, m, hf, s);
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2) {
+            f32x16 acc = {0};
+#pragma unroll
+            for (int cc = 0; cc < D / 16; ++cc)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ST::k_frag(kl, kb2, cc, m, hf), qf[cc], acc, 0, 0, 0);
+            s[kb2] = acc;
+        }
 
-        if (partial) {
-            const int* al = reinterpret_cast<const int*>(smem + SM::A_OFF) + buf * kTileK;
+        if (e_cur & RF_PLAN_PARTIAL) {
+            const int k0 = (e_cur & kTileIndexMask) * kTileK;
+            const int* al = side + (t % 3) * kTileK;
+            if (MODE == MODE_LISTED && !(e_cur & kTileBoundary)) {
+                // all 64 keys are video tokens: only the pattern's band decides
 #pragma unroll
-            for (int kb2 = 0; kb2 < 2; ++kb2)
+                for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int koff = 32 * kb2 + key_of_reg(r, hf);
-                    const int kidx = k0 + koff;
-                    bool ok = kidx < keyN;
-                    if (MODE == MODE_LISTED) {
-                        const int d = q_attr - al[koff];
-                        ok = ok && ((d < 0 ? -d : d) <= q_rad || kidx >= Nv);
+                    for (int r = 0; r < 16; ++r) {
+                        const uint32_t d = static_cast<uint32_t>(al[32 * kb2 + key_of_reg(r, hf)]) + q_lo;
+                        s[kb2][r] = d <= q_span ? s[kb2][r] : -INFINITY;
                     }
-                    s[kb2][r] = ok ? s[kb2][r] : -INFINITY;
-                }
+            } else {
+#pragma unroll
+                for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int koff = 32 * kb2 + key_of_reg(r, hf);
+                        const int kidx = k0 + koff;
+                        bool ok = kidx < keyN;
+                        if (MODE == MODE_LISTED) {
+                            const uint32_t d = static_cast<uint32_t>(al[koff]) + q_lo;
+                            ok = ok & ((d <= q_span) | (kidx >= Nv));
+                        }
+                        s[kb2][r] = ok ? s[kb2][r] : -INFINITY;
+                    }
+            }
         }
 
         // online softmax (Eq. 1), base-2 exponent with 1/sqrt(D) folded into c
@@ -240,9 +323,12 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(VT::frag(vl, db, u, m, hf), pf[u], oacc[db], 0, 0, 0);
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ST::v_frag(vl, db, u, m, hf), pf[u], oacc[db], 0, 0, 0);
 
         if (t + 1 < ntiles) stash_tile(t + 1);
+        if (t + 2 < ntiles) stash_side(t + 2);
+        e_cur = e_nxt;
+        e_nxt = e_nx2;
         __syncthreads();
     }
 
@@ -251,7 +337,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
     const float l_tot = l_run + other_half(l_run);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     if (qrow < N) {
-        uint16_t* orow = a.O + head_off + static_cast<size_t>(qrow) * D;
+        uint16_t* orow = a.O + static_cast<size_t>(qk.bh) * N * D + static_cast<size_t>(qrow) * D;
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -265,7 +351,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
 }
 
 template <int D, int NW>
-__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) attn_kernel(AttnArgs a) {
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW == 4 ? 2 : 1, 2))) attn_kernel(AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const DevicePlan& pl = a.plan;
     const int item = xcd_contiguous_item(blockIdx.x, pl.nQB * a.BH);
@@ -278,17 +364,17 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2)
     qk.cls = cls;
     qk.cols = nullptr;
     if (cls == RF_DENSE) {
-        qk.nblk = pl.nKB;
+        qk.ntiles = pl.nKT;
         qk.keyN = pl.N;
         attend<D, NW, MODE_ALL>(a, qk, smem);
     } else if (cls == RF_TEXTURAL && qk.qb < pl.first_text_qb) {
         // Textural query blocks made only of video tokens see the compacted key sequence
-        qk.nblk = pl.nCB;
+        qk.ntiles = pl.nCT;
         qk.keyN = pl.Nc;
         attend<D, NW, MODE_COMPACT>(a, qk, smem);
     } else {
         const int e0 = pl.row_ptr[cls][qk.qb];
-        qk.nblk = pl.row_ptr[cls][qk.qb + 1] - e0;
+        qk.ntiles = pl.row_ptr[cls][qk.qb + 1] - e0;
         qk.cols = pl.cols[cls] + e0;
         qk.keyN = pl.N;
         attend<D, NW, MODE_LISTED>(a, qk, smem);

@@ -11,6 +11,10 @@ namespace rf {
 
 constexpr int kTileK = 64;  // keys per LDS tile of the attention and ARM kernels
 
+// Flags on a key-tile entry of a block list (RF_PLAN_PARTIAL is public).
+constexpr int32_t kTileBoundary = 0x20000000;  // tile holds text keys or runs past the last key
+constexpr int32_t kTileIndexMask = 0x1fffffff;
+
 // Resolved, validated problem description.
 struct Geometry {
     int T, H, W, text_len;
@@ -24,12 +28,14 @@ struct Geometry {
 // Index 0/1/2 of the per-class arrays = Spatial / Temporal / Textural.
 struct HostPlan {
     Geometry g;
-    int block;     // skip-list granularity (64 or 128), also the query rows per workgroup
-    int nQB, nKB;  // ceil(N / block)
+    int block;     // query rows per block (64 or 128) = rows one workgroup owns
+    int nQB;       // ceil(N / block)
+    int nKT;       // ceil(N / kTileK): key tiles of the token sequence
     int Nc;        // compacted key count of the Textural pattern: kept video keys + text keys
-    int nCB;       // ceil(Nc / block)
+    int nCT;       // ceil(Nc / kTileK): key tiles of the compacted sequence
     int first_text_qb;  // first query block holding a text row (nQB if there is none)
-    std::vector<int32_t> row_ptr[3], cols[3];  // CSR block lists; Textural: text-holding query blocks only
+    // CSR lists of key tiles per query block; Textural: text-holding query blocks only
+    std::vector<int32_t> row_ptr[3], cols[3];
     std::vector<int32_t> attr[3];  // per token: frame index / in-frame index / 0 if kept by Eq. 4 else 1
     std::vector<int32_t> cidx;     // compacted position -> token index (Textural)
 };
@@ -51,7 +57,7 @@ struct DevicePlan {
     const int32_t* cidx;
     int radius[3];
     int N, Nv, Nc;
-    int block, nQB, nKB, nCB, first_text_qb;
+    int block, nQB, nKT, nCT, first_text_qb;
 };
 
 struct AttnArgs {

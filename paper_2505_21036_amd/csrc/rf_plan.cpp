@@ -1,9 +1,9 @@
 // Host-side block lists for RainFusion's three head patterns (Sec. 3.2).
 //
-// The masks are token-level predicates; this file only decides, for a square tiling of the
-// N x N score matrix, which (query block, key block) pairs contain at least one kept pair
-// (they are visited) and which of those contain a dropped pair or run past the last token
-// (the kernel re-applies the predicate there).  Everything is exact integer interval
+// The masks are token-level predicates; this file only decides, for a tiling of the N x N
+// score matrix into query blocks of `block` rows and key tiles of 64 columns, which pairs
+// contain at least one kept token pair (they are visited) and which of those contain a dropped
+// pair or run past the last token (the kernel re-applies the predicate there).  Everything is exact integer interval
 // arithmetic on frame indices and in-frame positions.
 #include <algorithm>
 #include <cmath>
@@ -67,7 +67,8 @@ void build_plan(const Geometry& g, int block, HostPlan* plan) {
     P.g = g;
     P.block = block;
     const int N = g.N, Nv = g.Nv, HW = g.HW;
-    P.nQB = P.nKB = (N + block - 1) / block;
+    P.nQB = (N + block - 1) / block;
+    P.nKT = (N + kTileK - 1) / kTileK;
     P.first_text_qb = g.text_len > 0 ? Nv / block : P.nQB;
 
     // per-token attributes
@@ -83,7 +84,7 @@ void build_plan(const Geometry& g, int block, HostPlan* plan) {
     }
     for (int n = Nv; n < N; ++n) P.cidx.push_back(n);
     P.Nc = static_cast<int>(P.cidx.size());
-    P.nCB = (P.Nc + block - 1) / block;
+    P.nCT = (P.Nc + kTileK - 1) / kTileK;
 
     std::vector<Span> qs, ks;
     for (int cls = 0; cls < 3; ++cls) {
@@ -97,8 +98,8 @@ void build_plan(const Geometry& g, int block, HostPlan* plan) {
             const bool q_text = q1 > Nv, q_video = q0 < Nv;
             if (cls == RF_TEXTURAL && !q_text) { rp[qb + 1] = static_cast<int32_t>(co.size()); continue; }
             if (cls == RF_TEMPORAL && q_video) position_spans(q0, qv1, HW, &qs);
-            for (int kb = 0; kb < P.nKB; ++kb) {
-                const int k0 = kb * block, k1 = std::min(N, k0 + block);
+            for (int kb = 0; kb < P.nKT; ++kb) {
+                const int k0 = kb * kTileK, k1 = std::min(N, k0 + kTileK);
                 const int kv1 = std::min(k1, Nv);
                 const bool k_text = k1 > Nv, k_video = k0 < Nv;
                 bool any = q_text || k_text, all = true;
@@ -126,8 +127,11 @@ void build_plan(const Geometry& g, int block, HostPlan* plan) {
                     }
                 }
                 if (!any) continue;
-                const bool tail = k0 + block > N;
-                co.push_back(kb | ((!all || tail) ? RF_PLAN_PARTIAL : 0));
+                const bool tail = k0 + kTileK > N;
+                // a tile of text keys only is never partial; one that mixes text and video keys, or
+                // runs past N, needs the position checks as well as the pattern's band check
+                const bool boundary = tail || (k_text && k_video && !all);
+                co.push_back(kb | ((!all || tail) ? RF_PLAN_PARTIAL : 0) | (boundary ? kTileBoundary : 0));
             }
             rp[qb + 1] = static_cast<int32_t>(co.size());
         }
@@ -139,12 +143,13 @@ void flatten_class(const HostPlan& P, int cls, std::vector<int32_t>* row_ptr, st
     cols->clear();
     for (int qb = 0; qb < P.nQB; ++qb) {
         if (cls == RF_DENSE || (cls == RF_TEXTURAL && qb < P.first_text_qb)) {
-            const int nb = cls == RF_DENSE ? P.nKB : P.nCB;
+            const int nt = cls == RF_DENSE ? P.nKT : P.nCT;
             const int len = cls == RF_DENSE ? P.g.N : P.Nc;
-            for (int kb = 0; kb < nb; ++kb)
-                cols->push_back(kb | ((kb + 1) * P.block > len ? RF_PLAN_PARTIAL : 0));
+            for (int kt = 0; kt < nt; ++kt)
+                cols->push_back(kt | ((kt + 1) * kTileK > len ? RF_PLAN_PARTIAL : 0));
         } else {
-            for (int e = P.row_ptr[cls][qb]; e < P.row_ptr[cls][qb + 1]; ++e) cols->push_back(P.cols[cls][e]);
+            for (int e = P.row_ptr[cls][qb]; e < P.row_ptr[cls][qb + 1]; ++e)
+                cols->push_back(P.cols[cls][e] & ~kTileBoundary);
         }
         (*row_ptr)[qb + 1] = static_cast<int32_t>(cols->size());
     }
