@@ -17,16 +17,88 @@ enum : int {
     MODE_LISTED = 2    // the CSR list of the head's pattern; partial tiles re-apply the predicate
 };
 
-// Global -> register -> LDS staging of one 64-key tile of K (row-major, padded rows) and of V
-// (transposed: one LDS row per channel, so the A operand of O^T = V^T P^T, eight consecutive
-// keys of one channel, is a single 16-byte read).
-//
-// A thread owns "units": unit (kg, dc) covers keys 8*kg .. 8*kg+7.  From V it loads channels
-// 4*dc .. 4*dc+3 of those 8 rows (8 bytes each) and transposes them in registers; from K it
-// loads 4 of the same 8 rows, 16 bytes each.  All row addresses of a unit therefore derive
-// from the same 8 tokens.
-template <int D, int NT>
-struct Stager {
+// Two ways of getting a 64-key tile of K and V from global memory into LDS and of reading
+// MFMA operands back out.  Both expose: init(), issue(), commit(), k_frag(), v_frag().
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+// (1) DirectTile, head_dim 64 and 128: global_load_lds writes the tile straight into LDS (no
+// staging registers).  A wavefront instruction fills 1 KiB of consecutive LDS, lane l bytes
+// 16*l .. 16*l+15, so rows are unpadded; bank conflicts are avoided by permuting, per row, which
+// 16-byte chunk of the row a slot holds (slot position = chunk ^ X(row)), which costs nothing
+// because every lane chooses its own global address.  K is read back 16 bytes per lane as the A
+// operand of S^T = K Q^T; V stays row-major [key][channel] and ds_read_b64_tr_b16 transposes it
+// on the way out into the A operand of O^T = V^T P^T (8 consecutive keys of one channel per lane).
+template <int D, int NW>
+struct DirectTile {
+    static_assert(D == 64 || D == 128, "row length must be a power of two number of 16-byte chunks");
+    static constexpr int NT = 64 * NW, CH = D / 8, ROW = 2 * D;
+    static constexpr int K_BYTES = kTileK * ROW, V_BYTES = kTileK * ROW;
+    static constexpr int SEGS = kTileK * CH / 64;  // 1 KiB segments per tile
+    static constexpr int PER_WAVE = SEGS / NW;     // load instructions per tensor per thread
+
+    // chunk permutation of a row: K spreads the 16 rows a read phase touches over all banks,
+    // V spreads the 4 rows a transposing read phase touches over the four 64-byte bank groups
+    static __device__ __forceinline__ int xk(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
+    static __device__ __forceinline__ int xv(int row) { return D == 128 ? 4 * (row & 3) : 4 * ((row >> 1) & 1); }
+
+    int wave, lane;
+    int k_base;          // byte offset of this lane's K operand for kb2 = 0, c = 0
+    int v_base[D / 32];  // byte offset of this lane's V operand for u = 0, first half, per channel block
+
+    __device__ __forceinline__ void init(int tid) {
+        lane = tid & 63;
+        wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const int hf = lane >> 5, m = lane & 31, g4 = lane >> 4, i = lane & 15;
+        const int krow = key_of_mfma_row(m);
+        k_base = krow * ROW + 16 * (hf ^ xk(krow));
+        const int vrow = 8 * hf + (i >> 2);  // + 16*u + 4*half: multiples of 4, invisible to xv()
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) {
+            const int chunk = 4 * db + 2 * (g4 & 1) + ((i & 3) >> 1);
+            v_base[db] = vrow * ROW + 16 * (chunk ^ xv(vrow)) + 8 * (i & 1);
+        }
+    }
+
+    // tok(row): token whose K/V row goes to tile row `row`; kh/vh: byte pointers the tokens index
+    template <typename F>
+    __device__ __forceinline__ void issue(const unsigned char* kh, const unsigned char* vh, unsigned char* kl,
+                                          unsigned char* vl, F tok) {
+#pragma unroll
+        for (int j = 0; j < PER_WAVE; ++j) {
+            const int seg = j * NW + wave;
+            const int slot = seg * 64 + lane, row = slot / CH, pos = slot % CH;
+            const uint32_t row_off = static_cast<uint32_t>(tok(row)) * ROW;
+            __builtin_amdgcn_global_load_lds(kh + row_off + 16 * (pos ^ xk(row)),
+                                             (__attribute__((address_space(3))) void*)(kl + seg * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(vh + row_off + 16 * (pos ^ xv(row)),
+                                             (__attribute__((address_space(3))) void*)(vl + seg * 1024), 16, 0, 0);
+        }
+    }
+    // the tile is in LDS once this thread's loads have landed (the barrier that follows publishes it)
+    __device__ __forceinline__ void commit(unsigned char*, unsigned char*) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+    __device__ __forceinline__ bf16x8 k_frag(const unsigned char* kl, int kb2, int c) const {
+        return as_bf16x8(*reinterpret_cast<const u32x4*>(kl + ((k_base ^ (32 * c)) + kb2 * 32 * ROW)));
+    }
+    __device__ __forceinline__ bf16x8 v_frag(const unsigned char* vl, int db, int u) const {
+        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+        const unsigned char* p = vl + v_base[db] + 16 * u * ROW;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * ROW));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, v);
+    }
+};
+
+// (2) StagedTile, any head_dim (used for 96): global -> registers -> LDS.  K rows are padded by
+// 16 bytes; V is transposed in registers and stored one LDS row per channel.  A thread owns
+// "units": unit (kg, dc) covers keys 8*kg .. 8*kg+7; from V it loads channels 4*dc .. 4*dc+3 of
+// those rows (8 bytes each), from K four of the same rows, 16 bytes each.
+template <int D, int NW>
+struct StagedTile {
+    static constexpr int NT = 64 * NW;
     static constexpr int K_ROW = 2 * D + 16;       // bytes; +16 pad: conflict-free 16-B reads down a column
     static constexpr int V_ROW = 2 * kTileK + 16;  // bytes
     static constexpr int K_BYTES = kTileK * K_ROW;
@@ -36,38 +108,41 @@ struct Stager {
     static constexpr int PER_THREAD = (UNITS + NT - 1) / NT;
     static constexpr bool EXACT = UNITS % NT == 0;
 
+    int tid, hf, m;
     u32x4 kreg[PER_THREAD][4];
     u32x2 vreg[PER_THREAD][8];
 
+    __device__ __forceinline__ void init(int t) {
+        tid = t;
+        hf = (t & 63) >> 5;
+        m = t & 31;
+    }
     static __device__ __forceinline__ int k_row_in_group(int dc) { return 4 * (dc / (D / 8)); }
     static __device__ __forceinline__ int k_chunk(int dc) { return dc % (D / 8); }
 
-    // vtok(i, e): token of key 8*kg + e of this thread's unit i (e = 0..7); ktok(i, j): token of
-    // the j-th K row of the unit (key 8*kg + k_row_in_group(dc) + j, j = 0..3).  Offsets are
-    // 32-bit byte offsets from the base pointers (a head is < 4 GiB).
-    template <typename FV, typename FK>
-    __device__ __forceinline__ void fetch(const unsigned char* kbase, const unsigned char* vbase, int tid, FV vtok,
-                                          FK ktok) {
+    template <typename F>
+    __device__ __forceinline__ void issue(const unsigned char* kh, const unsigned char* vh, unsigned char*,
+                                          unsigned char*, F tok) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             const int u = tid + i * NT;
             if (EXACT || u < UNITS) {
-                const int dc = u % DC;
+                const int kg = u / DC, dc = u % DC;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const uint32_t row_off = static_cast<uint32_t>(vtok(i, e)) * (2u * D);
-                    vreg[i][e] = *reinterpret_cast<const u32x2*>(vbase + row_off + 8u * dc);
+                    const uint32_t row_off = static_cast<uint32_t>(tok(8 * kg + e)) * (2u * D);
+                    vreg[i][e] = *reinterpret_cast<const u32x2*>(vh + row_off + 8u * dc);
                 }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const uint32_t row_off = static_cast<uint32_t>(ktok(i, j)) * (2u * D);
-                    kreg[i][j] = *reinterpret_cast<const u32x4*>(kbase + row_off + 16u * k_chunk(dc));
+                    const uint32_t row_off = static_cast<uint32_t>(tok(8 * kg + k_row_in_group(dc) + j)) * (2u * D);
+                    kreg[i][j] = *reinterpret_cast<const u32x4*>(kh + row_off + 16u * k_chunk(dc));
                 }
             }
         }
     }
 
-    __device__ __forceinline__ void stash(unsigned char* kl, unsigned char* vl, int tid) const {
+    __device__ __forceinline__ void commit(unsigned char* kl, unsigned char* vl) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             const int u = tid + i * NT;
@@ -98,21 +173,34 @@ struct Stager {
     }
 
     // A operand of S^T = K Q^T: keys 32*kb2 .. +31 (permuted per lane), channels 16*c + 8*hf .. +7
-    static __device__ __forceinline__ bf16x8 k_frag(const unsigned char* kl, int kb2, int c, int m, int hf) {
+    __device__ __forceinline__ bf16x8 k_frag(const unsigned char* kl, int kb2, int c) const {
         const int row = 32 * kb2 + key_of_mfma_row(m);
         return as_bf16x8(*reinterpret_cast<const u32x4*>(kl + row * K_ROW + 32 * c + 16 * hf));
     }
     // A operand of O^T = V^T P^T: channels 32*db + m, keys 16*u + 8*hf .. +7
-    static __device__ __forceinline__ bf16x8 v_frag(const unsigned char* vl, int db, int u, int m, int hf) {
+    __device__ __forceinline__ bf16x8 v_frag(const unsigned char* vl, int db, int u) const {
         const int row = 32 * db + m;
         const int pos = (2 * u + hf) ^ ((row >> 4) & 3);
         return as_bf16x8(*reinterpret_cast<const u32x4*>(vl + row * V_ROW + 16 * pos));
     }
 };
 
-template <int D, int NT>
+template <int D, int NW>
+struct TileFor {
+    using type = StagedTile<D, NW>;
+};
+template <int NW>
+struct TileFor<64, NW> {
+    using type = DirectTile<64, NW>;
+};
+template <int NW>
+struct TileFor<128, NW> {
+    using type = DirectTile<128, NW>;
+};
+
+template <int D, int NW>
 struct AttnSmem {
-    using ST = Stager<D, NT>;
+    using ST = typename TileFor<D, NW>::type;
     static constexpr int K_OFF = 0;
     static constexpr int V_OFF = 2 * ST::K_BYTES;
     static constexpr int SIDE_OFF = V_OFF + 2 * ST::V_BYTES;  // ring of 3 x 64 ints: key indices or key attributes
@@ -132,9 +220,9 @@ constexpr float kRescaleSlack = 8.f;
 
 template <int D, int NW, int MODE>
 __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, unsigned char* smem) {
-    constexpr int NT = 64 * NW, BQ = 32 * NW;
-    using ST = Stager<D, NT>;
-    using SM = AttnSmem<D, NT>;
+    constexpr int BQ = 32 * NW;
+    using ST = typename TileFor<D, NW>::type;
+    using SM = AttnSmem<D, NW>;
     const DevicePlan& pl = a.plan;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, m = lane & 31;
     const int N = pl.N, Nv = pl.Nv, keyN = qk.keyN, ntiles = qk.ntiles;
@@ -170,6 +258,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
     const float c = a.scale_log2;
 
     ST st;
+    st.init(tid);
     int side_reg = 0;
 
     auto entry_of = [&](int t) -> int {
@@ -185,29 +274,22 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
         if (MODE == MODE_ALL) return;
         if (tid < kTileK) side[(t % 3) * kTileK + tid] = side_reg;
     };
-    // first key of unit i's key group inside the tile, and first K row of the unit inside the group
-    auto group_key = [&](int i) { return 8 * (((tid + i * NT) / ST::DC) & 7); };
-    auto k_first = [&](int i) { return ST::k_row_in_group((tid + i * NT) % ST::DC); };
+    auto k_lds = [&](int t) { return smem + SM::K_OFF + (t & 1) * ST::K_BYTES; };
+    auto v_lds = [&](int t) { return smem + SM::V_OFF + (t & 1) * ST::V_BYTES; };
     auto fetch_tile = [&](int t, int entry) {
         const int k0 = (entry & kTileIndexMask) * kTileK;
         if (MODE == MODE_COMPACT) {
             const int* idx = side + (t % 3) * kTileK;
-            st.fetch(Kh, Vh, tid, [&](int i, int e) { return idx[group_key(i) + e]; },
-                     [&](int i, int j) { return idx[group_key(i) + k_first(i) + j]; });
+            st.issue(Kh, Vh, k_lds(t), v_lds(t), [&](int row) { return idx[row]; });
         } else if (k0 + kTileK <= keyN) {
             // full tile: rows are consecutive tokens, everything but the tile origin is loop invariant
-            const unsigned char* kb = Kh + static_cast<size_t>(k0) * (2 * D);
-            const unsigned char* vb = Vh + static_cast<size_t>(k0) * (2 * D);
-            st.fetch(kb, vb, tid, [&](int i, int e) { return group_key(i) + e; },
-                     [&](int i, int j) { return group_key(i) + k_first(i) + j; });
+            const size_t origin = static_cast<size_t>(k0) * (2 * D);
+            st.issue(Kh + origin, Vh + origin, k_lds(t), v_lds(t), [&](int row) { return row; });
         } else {
-            st.fetch(Kh, Vh, tid, [&](int i, int e) { return min(k0 + group_key(i) + e, keyN - 1); },
-                     [&](int i, int j) { return min(k0 + group_key(i) + k_first(i) + j, keyN - 1); });
+            st.issue(Kh, Vh, k_lds(t), v_lds(t), [&](int row) { return min(k0 + row, keyN - 1); });
         }
     };
-    auto stash_tile = [&](int t) {
-        st.stash(smem + SM::K_OFF + (t & 1) * ST::K_BYTES, smem + SM::V_OFF + (t & 1) * ST::V_BYTES, tid);
-    };
+    auto stash_tile = [&](int t) { st.commit(k_lds(t), v_lds(t)); };
 
     // software pipeline: side data runs two tiles ahead of the compute, K/V one tile ahead
     int e_cur = 0, e_nxt = 0, e_nx2 = 0;
@@ -243,7 +325,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
             f32x16 acc = {0};
 #pragma unroll
             for (int cc = 0; cc < D / 16; ++cc)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ST::k_frag(kl, kb2, cc, m, hf), qf[cc], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st.k_frag(kl, kb2, cc), qf[cc], acc, 0, 0, 0);
             s[kb2] = acc;
         }
 
@@ -323,7 +405,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ST::v_frag(vl, db, u, m, hf), pf[u], oacc[db], 0, 0, 0);
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st.v_frag(vl, db, u), pf[u], oacc[db], 0, 0, 0);
 
         if (t + 1 < ntiles) stash_tile(t + 1);
         if (t + 2 < ntiles) stash_side(t + 2);
@@ -384,7 +466,7 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW
 template <int D, int NW>
 static int launch_one(const AttnArgs& a, hipStream_t st) {
     constexpr int NT = 64 * NW;
-    constexpr int smem = AttnSmem<D, NT>::BYTES;
+    constexpr int smem = AttnSmem<D, NW>::BYTES;
     static bool configured = false;  // raising the dynamic-LDS limit is per function, once
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<D, NW>),
