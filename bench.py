@@ -213,7 +213,7 @@ def main():
         ol = orc.Layout(w.T, w.H, w.W, w.text_len)
         q, k, v = (t.float().numpy() for t in inp.head_qkv(w, 0, 0))
         nthreads = orc.num_threads()
-        rows = np.array(inp.sample_rows(w, 64 * nthreads))
+        rows = np.array(inp.sample_rows(w, 1536 * nthreads))  # ~10-30 s of oracle time
         cls0 = classes_host[0]
         orc.attention_rows(q, k, v, cls0, ol, orc.Params(), rows[:nthreads])  # warm the library / threads
         t0 = time.perf_counter()
