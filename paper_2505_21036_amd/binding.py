@@ -16,7 +16,7 @@ RF_PLAN_PARTIAL = 0x40000000
 RF_KEY_TILE = 64
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "librainfusion.so")
+_LIB_PATH = os.environ.get("RF_LIBRARY") or os.path.join(_HERE, "librainfusion.so")
 _lib = None
 
 

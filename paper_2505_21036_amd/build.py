@@ -18,12 +18,12 @@ def hipcc():
     raise RuntimeError("hipcc not found")
 
 
-def build_library(verbose=False):
+def build_library(verbose=False, extra_flags=(), out=LIB):
     """Compile every source for gfx950 and link the shared library. Always rebuilds."""
     objs = []
     flags = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"),
              "-I", CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
-             "-Wno-unused-command-line-argument"]
+             "-Wno-unused-command-line-argument"] + list(extra_flags)
     procs = []
     for s in SOURCES:
         obj = os.path.join(CSRC, os.path.splitext(s)[0] + ".o")
@@ -37,10 +37,10 @@ def build_library(verbose=False):
             raise RuntimeError("hipcc failed on %s:\n%s" % (s, err))
         if verbose and err.strip():
             sys.stderr.write(err + "\n")
-    tmp = LIB + ".tmp%d" % os.getpid()
+    tmp = out + ".tmp%d" % os.getpid()
     subprocess.check_call([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":

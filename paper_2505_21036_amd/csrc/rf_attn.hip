@@ -42,9 +42,25 @@ struct DirectTile {
     static __device__ __forceinline__ int xk(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
     static __device__ __forceinline__ int xv(int row) { return D == 128 ? 4 * (row & 3) : 4 * ((row >> 1) & 1); }
 
+    static __device__ __forceinline__ uint32_t lds_offset(const unsigned char* p) {
+        return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const unsigned char*)p));
+    }
+    // One 16-byte-per-lane load from  base + lane offset  into LDS at  lds_addr + 16*lane; completion
+    // is awaited in commit().
+    static __device__ __forceinline__ void dma16(const unsigned char* base, uint32_t lane_off, uint32_t lds_addr) {
+        __builtin_amdgcn_global_load_lds(base + lane_off, (__attribute__((address_space(3))) void*)(uintptr_t)lds_addr, 16,
+                                         0, 0);
+    }
+
     int wave, lane;
     int k_base;          // byte offset of this lane's K operand for kb2 = 0, c = 0
     int v_base[D / 32];  // byte offset of this lane's V operand for u = 0, first half, per channel block
+    static constexpr int ROWS_PER_LOAD = 64 * NW / CH;  // tile rows between a thread's successive loads
+    // X(row) has period 16 for K and 4 for V, so V's lane offset never depends on the load index j
+    // and K's only when a load covers fewer than 16 rows
+    static constexpr int K_VARIANTS = (ROWS_PER_LOAD % 16 == 0) ? 1 : PER_WAVE;
+    static_assert(ROWS_PER_LOAD % 4 == 0, "V row permutation must not change between loads");
+    uint32_t k_lane_off[K_VARIANTS], v_lane_off;  // global byte offsets of this lane's slot within a load
 
     __device__ __forceinline__ void init(int tid) {
         lane = tid & 63;
@@ -52,6 +68,13 @@ struct DirectTile {
         const int hf = lane >> 5, m = lane & 31, g4 = lane >> 4, i = lane & 15;
         const int krow = key_of_mfma_row(m);
         k_base = krow * ROW + 16 * (hf ^ xk(krow));
+        {
+            // slot of load j: tile row  j*ROWS_PER_LOAD + row0, position pos; X(row) is the same for all j
+            const int slot = wave * 64 + lane, row0 = slot / CH, pos = slot % CH;
+#pragma unroll
+            for (int j = 0; j < K_VARIANTS; ++j) k_lane_off[j] = row0 * ROW + 16 * (pos ^ xk(row0 + j * ROWS_PER_LOAD));
+            v_lane_off = row0 * ROW + 16 * (pos ^ xv(row0));
+        }
         const int vrow = 8 * hf + (i >> 2);  // + 16*u + 4*half: multiples of 4, invisible to xv()
 #pragma unroll
         for (int db = 0; db < D / 32; ++db) {
@@ -69,10 +92,19 @@ struct DirectTile {
             const int seg = j * NW + wave;
             const int slot = seg * 64 + lane, row = slot / CH, pos = slot % CH;
             const uint32_t row_off = static_cast<uint32_t>(tok(row)) * ROW;
-            __builtin_amdgcn_global_load_lds(kh + row_off + 16 * (pos ^ xk(row)),
-                                             (__attribute__((address_space(3))) void*)(kl + seg * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(vh + row_off + 16 * (pos ^ xv(row)),
-                                             (__attribute__((address_space(3))) void*)(vl + seg * 1024), 16, 0, 0);
+            const uint32_t k_off = row_off + 16u * (pos ^ xk(row)), v_off = row_off + 16u * (pos ^ xv(row));
+            dma16(kh, k_off, lds_offset(kl) + seg * 1024);
+            dma16(vh, v_off, lds_offset(vl) + seg * 1024);
+        }
+    }
+    // same for a tile of 64 consecutive tokens starting at kh / vh: only uniform bases move
+    __device__ __forceinline__ void issue_consecutive(const unsigned char* kh, const unsigned char* vh, unsigned char* kl,
+                                                      unsigned char* vl) {
+#pragma unroll
+        for (int j = 0; j < PER_WAVE; ++j) {
+            const int seg = j * NW + wave;
+            dma16(kh + j * ROWS_PER_LOAD * ROW, k_lane_off[j % K_VARIANTS], lds_offset(kl) + seg * 1024);
+            dma16(vh + j * ROWS_PER_LOAD * ROW, v_lane_off, lds_offset(vl) + seg * 1024);
         }
     }
     // the tile is in LDS once this thread's loads have landed (the barrier that follows publishes it)
@@ -140,6 +172,11 @@ struct StagedTile {
                 }
             }
         }
+    }
+
+    __device__ __forceinline__ void issue_consecutive(const unsigned char* kh, const unsigned char* vh, unsigned char* kl,
+                                                      unsigned char* vl) {
+        issue(kh, vh, kl, vl, [](int row) { return row; });
     }
 
     __device__ __forceinline__ void commit(unsigned char* kl, unsigned char* vl) {
@@ -253,25 +290,45 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
     f32x16 oacc[D / 32];
 #pragma unroll
     for (int db = 0; db < D / 32; ++db) oacc[db] = f32x16{0};
-    // m_ref: reference subtracted inside exp2 (in units of raw score); l_run: this lane's share of the denominator
-    float m_ref = -INFINITY, l_run = 0.f;
+    // m_ref: reference subtracted inside exp2 (raw score units), finite from the start; has_ref: it has
+    // been taken from real scores of this row; l_run: this lane's share of the softmax denominator
+    float m_ref = 0.f, l_run = 0.f;
+    bool has_ref = false;
     const float c = a.scale_log2;
 
     ST st;
     st.init(tid);
     int side_reg = 0;
 
+    // Tile entries of a listed query block are read 64 at a time, one per lane, and handed out with
+    // v_readlane: no scalar-load latency in the loop.  ent_cur covers [ent_base, ent_base + 64).
+    int ent_cur = 0, ent_nxt = 0, ent_base = 0;
+    auto load_entries = [&](int first) { return qk.cols[min(first + lane, ntiles - 1)]; };
+    if (MODE == MODE_LISTED && ntiles > 0) {
+        ent_cur = load_entries(0);
+        ent_nxt = load_entries(64);
+    }
+    // entries must be asked for in increasing t
     auto entry_of = [&](int t) -> int {
-        if (MODE == MODE_LISTED) return qk.cols[t];
+        if (MODE == MODE_LISTED) {
+            if (t >= ent_base + 64) {
+                ent_base += 64;
+                ent_cur = ent_nxt;
+                ent_nxt = load_entries(ent_base + 64);
+            }
+            return __builtin_amdgcn_readlane(ent_cur, t - ent_base);
+        }
         return t | ((t + 1) * kTileK > keyN ? (RF_PLAN_PARTIAL | kTileBoundary) : 0);
     };
+    // side data is needed for every tile of the compacted sequence, and for partial listed tiles
+    auto wants_side = [&](int entry) { return MODE == MODE_COMPACT || (MODE == MODE_LISTED && (entry & RF_PLAN_PARTIAL)); };
     auto load_side = [&](int entry) {
-        if (MODE == MODE_ALL) return;
+        if (!wants_side(entry)) return;
         const int k0 = (entry & kTileIndexMask) * kTileK;
         if (tid < kTileK) side_reg = side_src[min(k0 + tid, keyN - 1)];
     };
-    auto stash_side = [&](int t) {
-        if (MODE == MODE_ALL) return;
+    auto stash_side = [&](int t, int entry) {
+        if (!wants_side(entry)) return;
         if (tid < kTileK) side[(t % 3) * kTileK + tid] = side_reg;
     };
     auto k_lds = [&](int t) { return smem + SM::K_OFF + (t & 1) * ST::K_BYTES; };
@@ -284,42 +341,16 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
         } else if (k0 + kTileK <= keyN) {
             // full tile: rows are consecutive tokens, everything but the tile origin is loop invariant
             const size_t origin = static_cast<size_t>(k0) * (2 * D);
-            st.issue(Kh + origin, Vh + origin, k_lds(t), v_lds(t), [&](int row) { return row; });
+            st.issue_consecutive(Kh + origin, Vh + origin, k_lds(t), v_lds(t));
         } else {
             st.issue(Kh, Vh, k_lds(t), v_lds(t), [&](int row) { return min(k0 + row, keyN - 1); });
         }
     };
     auto stash_tile = [&](int t) { st.commit(k_lds(t), v_lds(t)); };
 
-    // software pipeline: side data runs two tiles ahead of the compute, K/V one tile ahead
-    int e_cur = 0, e_nxt = 0, e_nx2 = 0;
-    if (ntiles > 0) {
-        e_cur = entry_of(0);
-        if (ntiles > 1) e_nxt = entry_of(1);
-        load_side(e_cur);
-        stash_side(0);
-        if (ntiles > 1) {
-            load_side(e_nxt);
-            stash_side(1);
-        }
-    }
-    __syncthreads();
-    if (ntiles > 0) {
-        fetch_tile(0, e_cur);
-        stash_tile(0);
-    }
-    __syncthreads();
-
-    for (int t = 0; t < ntiles; ++t) {
-        const int buf = t & 1;
-        if (t + 2 < ntiles) e_nx2 = entry_of(t + 2);
-        if (t + 1 < ntiles) fetch_tile(t + 1, e_nxt);
-        if (t + 2 < ntiles) load_side(e_nx2);
-
-        const unsigned char* kl = smem + SM::K_OFF + buf * ST::K_BYTES;
-        const unsigned char* vl = smem + SM::V_OFF + buf * ST::V_BYTES;
-
-        f32x16 s[2];
+    // S^T of tile t (64 keys x this lane's query), predicate applied where the tile is partial
+    auto scores = [&](int t, int entry, f32x16 (&s)[2]) {
+        const unsigned char* kl = k_lds(t);
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2) {
             f32x16 acc = {0};
@@ -328,11 +359,10 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st.k_frag(kl, kb2, cc), qf[cc], acc, 0, 0, 0);
             s[kb2] = acc;
         }
-
-        if (e_cur & RF_PLAN_PARTIAL) {
-            const int k0 = (e_cur & kTileIndexMask) * kTileK;
+        if (entry & RF_PLAN_PARTIAL) {
+            const int k0 = (entry & kTileIndexMask) * kTileK;
             const int* al = side + (t % 3) * kTileK;
-            if (MODE == MODE_LISTED && !(e_cur & kTileBoundary)) {
+            if (MODE == MODE_LISTED && !(entry & kTileBoundary)) {
                 // all 64 keys are video tokens: only the pattern's band decides
 #pragma unroll
                 for (int kb2 = 0; kb2 < 2; ++kb2)
@@ -357,50 +387,89 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
                     }
             }
         }
+    };
+    // p = exp2((s - m_ref) * c) in place; returns this lane's sum
+    auto exponentiate = [&](f32x16 (&s)[2]) {
+        const float mc = m_ref * c;
+        float sum = 0.f;
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                s[kb2][r] = fast_exp2(fmaf(s[kb2][r], c, -mc));
+                sum += s[kb2][r];
+            }
+        return sum;
+    };
 
-        // online softmax (Eq. 1), base-2 exponent with 1/sqrt(D) folded into c
+    // software pipeline: side data runs two tiles ahead of the compute, K/V one tile ahead
+    int e_cur = 0, e_nxt = 0, e_nx2 = 0;
+    if (ntiles > 0) {
+        e_cur = entry_of(0);
+        if (ntiles > 1) e_nxt = entry_of(1);
+        load_side(e_cur);
+        stash_side(0, e_cur);
+        if (ntiles > 1) {
+            load_side(e_nxt);
+            stash_side(1, e_nxt);
+        }
+    }
+    __syncthreads();
+    if (ntiles > 0) {
+        fetch_tile(0, e_cur);
+        stash_tile(0);
+    }
+    __syncthreads();
+
+    for (int t = 0; t < ntiles; ++t) {
+        if (t + 2 < ntiles) e_nx2 = entry_of(t + 2);
+        if (t + 1 < ntiles) fetch_tile(t + 1, e_nxt);
+        if (t + 2 < ntiles) load_side(e_nx2);
+
+        // Online softmax (Eq. 1) in base 2 with 1/sqrt(D) folded into c.  The reference subtracted in
+        // the exponent is moved, and the accumulators rescaled, only when a row outgrows it by more
+        // than 2^kRescaleSlack (or has none yet): the softmax does not depend on the reference.
+        f32x16 s[2];
+        scores(t, e_cur, s);
         float mt = s[0][0];
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
             for (int r = 0; r < 16; ++r) mt = fmaxf(mt, s[kb2][r]);
-        mt = fmaxf(mt, other_half(mt));
-        // move the reference only when some row of this wavefront outgrew it by more than the slack
-        const bool grow = (mt - m_ref) * c > kRescaleSlack || (m_ref == -INFINITY && mt > -INFINITY);
+        // the two halves of the wavefront hold different keys of the same 32 queries: their maxima
+        // are exchanged only when some lane asks for the reference to move
+        const bool grow = has_ref ? (mt - m_ref) * c > kRescaleSlack : mt > -INFINITY;
         if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-            const float m_new = fmaxf(m_ref, mt);
-            const float m_use = m_new == -INFINITY ? 0.f : m_new;
-            const float alpha = fast_exp2((m_ref - m_use) * c);
-            l_run *= alpha;
+            mt = fmaxf(mt, other_half(mt));
+            if (mt > -INFINITY) {
+                const float m_new = has_ref ? fmaxf(m_ref, mt) : mt;
+                const float alpha = has_ref ? fast_exp2((m_ref - m_new) * c) : 0.f;  // nothing accumulated before
+                l_run *= alpha;
 #pragma unroll
-            for (int db = 0; db < D / 32; ++db)
+                for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-            m_ref = m_new;
+                    for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+                m_ref = m_new;
+                has_ref = true;
+            }
         }
-        const float mc = (m_ref == -INFINITY ? 0.f : m_ref) * c;
-        float psum = 0.f;
+        const float psum = exponentiate(s);
+        l_run += psum;
+
         bf16x8 pf[4];
 #pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2) {
-            float p[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                p[r] = fast_exp2(fmaf(s[kb2][r], c, -mc));
-                psum += p[r];
-            }
+        for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
             for (int u2 = 0; u2 < 2; ++u2) {
                 u32x4 w;
-                w.x = pack_bf16(p[8 * u2 + 0], p[8 * u2 + 1]);
-                w.y = pack_bf16(p[8 * u2 + 2], p[8 * u2 + 3]);
-                w.z = pack_bf16(p[8 * u2 + 4], p[8 * u2 + 5]);
-                w.w = pack_bf16(p[8 * u2 + 6], p[8 * u2 + 7]);
+                w.x = pack_bf16(s[kb2][8 * u2 + 0], s[kb2][8 * u2 + 1]);
+                w.y = pack_bf16(s[kb2][8 * u2 + 2], s[kb2][8 * u2 + 3]);
+                w.z = pack_bf16(s[kb2][8 * u2 + 4], s[kb2][8 * u2 + 5]);
+                w.w = pack_bf16(s[kb2][8 * u2 + 6], s[kb2][8 * u2 + 7]);
                 pf[2 * kb2 + u2] = as_bf16x8(w);
             }
-        }
-        l_run += psum;
 
+        const unsigned char* vl = v_lds(t);
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -408,7 +477,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
                 oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st.v_frag(vl, db, u), pf[u], oacc[db], 0, 0, 0);
 
         if (t + 1 < ntiles) stash_tile(t + 1);
-        if (t + 2 < ntiles) stash_side(t + 2);
+        if (t + 2 < ntiles) stash_side(t + 2, e_nx2);
         e_cur = e_nxt;
         e_nxt = e_nx2;
         __syncthreads();
