@@ -50,7 +50,7 @@ def main():
     ap.add_argument("--workload", default="hunyuan720p")
     ap.add_argument("--block", type=int, default=0, help="skip-list block (64|128); 0 = the workload's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", default="", help="profiling aid: run just 'step', 'arm', 'thirds' or 'dense'")
+    ap.add_argument("--only", default="", help="profiling aid: run just 'step', 'arm', 'thirds', 'dense', or every head 'spatial' / 'temporal' / 'textural'")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
@@ -96,7 +96,11 @@ def main():
         return sum(a.elapsed_time(b) for a, b in pairs) / reps
 
     if args.only:
-        fn = {"step": step, "arm": arm, "thirds": lambda: attn(thirds), "dense": lambda: attn(dense)}[args.only]
+        one = {n: torch.full((w.B, w.nH), c, dtype=torch.int32, device=dev)
+               for n, c in (("spatial", rf.RF_SPATIAL), ("temporal", rf.RF_TEMPORAL), ("textural", rf.RF_TEXTURAL))}
+        fn = {"step": step, "arm": arm, "thirds": lambda: attn(thirds), "dense": lambda: attn(dense),
+              "spatial": lambda: attn(one["spatial"]), "temporal": lambda: attn(one["temporal"]),
+              "textural": lambda: attn(one["textural"])}[args.only]
         arm()
         for _ in range(args.warmup):
             fn()

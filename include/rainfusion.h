@@ -118,6 +118,14 @@ int rf_sparse_attention(const void *Q, const void *K, const void *V, const int32
 int rf_plan_host(const rf_layout *layout, const rf_params *params, int block, int cls,
                  int32_t *row_ptr, int32_t *cols, size_t cap, size_t *needed);
 
+/*
+ * Host-side view of the order in which rf_sparse_attention hands a head's query blocks to
+ * workgroups under pattern `cls` (a scheduling detail: it affects cache behaviour and load
+ * balance, never the result).  order: host, int32 [nQB], receives a permutation of 0..nQB-1.
+ * RF_DENSE heads use the identity.
+ */
+int rf_plan_order(const rf_layout *layout, const rf_params *params, int block, int cls, int32_t *order);
+
 /* Drop every cached block list and free its device memory (synchronises the device). */
 int rf_plan_clear(void);
 

@@ -66,6 +66,8 @@ def load_library():
     lib.rf_sparse_attention.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, PL, PP, C.c_int, vp, vp]
     lib.rf_plan_host.restype = C.c_int
     lib.rf_plan_host.argtypes = [PL, PP, C.c_int, C.c_int, vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
+    lib.rf_plan_order.restype = C.c_int
+    lib.rf_plan_order.argtypes = [PL, PP, C.c_int, C.c_int, vp]
     lib.rf_plan_clear.restype = C.c_int
     lib.rf_plan_clear.argtypes = []
     _lib = lib
@@ -165,6 +167,16 @@ def rf_plan_host(layout, params, block, cls):
     if st != 0:
         raise RfError(st, "rf_plan_host")
     return row_ptr, cols[:needed.value]
+
+
+def rf_plan_order(layout, params, block, cls):
+    """Order in which a head's query blocks are handed to workgroups: int32 permutation of 0..nQB-1."""
+    N = layout.T * layout.H * layout.W + layout.text_len
+    order = np.full((N + block - 1) // block, -1, dtype=np.int32)
+    st = load_library().rf_plan_order(C.byref(layout), _pp(params), block, cls, order.ctypes.data)
+    if st != 0:
+        raise RfError(st, "rf_plan_order")
+    return order
 
 
 def plan_block_counts(layout, params, block, cls):

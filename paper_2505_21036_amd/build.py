@@ -23,7 +23,7 @@ def build_library(verbose=False, extra_flags=(), out=LIB):
     objs = []
     flags = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"),
              "-I", CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
-             "-Wno-unused-command-line-argument"] + list(extra_flags)
+             "-Wno-unused-command-line-argument", "-DRF_SCHED_QK=4", "-DRF_SCHED_PV=3"] + list(extra_flags)
     procs = []
     for s in SOURCES:
         obj = os.path.join(CSRC, os.path.splitext(s)[0] + ".o")

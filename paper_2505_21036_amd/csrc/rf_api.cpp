@@ -68,11 +68,12 @@ int get_attention_plan(const Geometry& g, int block, const DevicePlan** out) {
         HostPlan hp;
         build_plan(g, block, &hp);
         BlobBuilder bb;
-        size_t off_rp[3], off_co[3], off_at[3];
+        size_t off_rp[3], off_co[3], off_at[3], off_qo[3];
         for (int c = 0; c < 3; ++c) {
             off_rp[c] = bb.add(hp.row_ptr[c]);
             off_co[c] = bb.add(hp.cols[c]);
             off_at[c] = bb.add(hp.attr[c]);
+            off_qo[c] = bb.add(hp.qorder[c]);
         }
         const size_t off_ci = bb.add(hp.cidx);
         auto p = std::make_unique<CachedPlan>();
@@ -87,6 +88,7 @@ int get_attention_plan(const Geometry& g, int block, const DevicePlan** out) {
             d.row_ptr[c] = base + off_rp[c];
             d.cols[c] = base + off_co[c];
             d.attr[c] = base + off_at[c];
+            d.qorder[c] = base + off_qo[c];
         }
         d.cidx = base + off_ci;
         d.radius[RF_SPATIAL] = g.r_spatial;
@@ -256,6 +258,19 @@ int rf_plan_host(const rf_layout* layout, const rf_params* params, int block, in
         if (cap < co.size()) return RF_ERR_WORKSPACE;
         std::memcpy(cols, co.data(), co.size() * sizeof(int32_t));
     }
+    return RF_OK;
+}
+
+int rf_plan_order(const rf_layout* layout, const rf_params* params, int block, int cls, int32_t* order) {
+    if (!layout || !order) return RF_ERR_NULL;
+    Geometry g;
+    const int st = resolve_geometry(layout, params, &g);
+    if (st != RF_OK) return st;
+    if (block != 64 && block != 128) return RF_ERR_BLOCK;
+    if (cls < RF_SPATIAL || cls > RF_DENSE) return RF_ERR_PARAM;
+    HostPlan hp;
+    build_plan(g, block, &hp);
+    for (int i = 0; i < hp.nQB; ++i) order[i] = cls == RF_DENSE ? i : hp.qorder[cls][i];
     return RF_OK;
 }
 

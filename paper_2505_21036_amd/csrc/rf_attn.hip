@@ -35,6 +35,7 @@ struct DirectTile {
     static constexpr int NT = 64 * NW, CH = D / 8, ROW = 2 * D;
     static constexpr int K_BYTES = kTileK * ROW, V_BYTES = kTileK * ROW;
     static constexpr int SEGS = kTileK * CH / 64;  // 1 KiB segments per tile
+    static constexpr int V_READS_PER_FRAG = 2;
     static constexpr int PER_WAVE = SEGS / NW;     // load instructions per tensor per thread
 
     // chunk permutation of a row: K spreads the 16 rows a read phase touches over all banks,
@@ -136,6 +137,7 @@ struct StagedTile {
     static constexpr int K_BYTES = kTileK * K_ROW;
     static constexpr int V_BYTES = D * V_ROW;
     static constexpr int DC = D / 4;               // units per key group
+    static constexpr int V_READS_PER_FRAG = 1;
     static constexpr int UNITS = (kTileK / 8) * DC;
     static constexpr int PER_THREAD = (UNITS + NT - 1) / NT;
     static constexpr bool EXACT = UNITS % NT == 0;
@@ -359,6 +361,16 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st.k_frag(kl, kb2, cc), qf[cc], acc, 0, 0, 0);
             s[kb2] = acc;
         }
+#ifdef RF_SCHED_QK
+        // keep RF_SCHED_QK operand reads in flight ahead of the MFMA that consumes them
+        __builtin_amdgcn_sched_group_barrier(0x100, RF_SCHED_QK, 0);
+#pragma unroll
+        for (int i = 0; i < 2 * (D / 16) - RF_SCHED_QK; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, RF_SCHED_QK, 0);
+#endif
         if (entry & RF_PLAN_PARTIAL) {
             const int k0 = (entry & kTileIndexMask) * kTileK;
             const int* al = side + (t % 3) * kTileK;
@@ -475,6 +487,18 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
 #pragma unroll
             for (int u = 0; u < 4; ++u)
                 oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st.v_frag(vl, db, u), pf[u], oacc[db], 0, 0, 0);
+#ifdef RF_SCHED_PV
+        {
+            constexpr int PER = ST::V_READS_PER_FRAG, TOTAL = 4 * (D / 32);
+            __builtin_amdgcn_sched_group_barrier(0x100, RF_SCHED_PV * PER, 1);
+#pragma unroll
+            for (int i = 0; i < TOTAL - RF_SCHED_PV; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+                __builtin_amdgcn_sched_group_barrier(0x100, PER, 1);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, RF_SCHED_PV, 1);
+        }
+#endif
 
         if (t + 1 < ntiles) stash_tile(t + 1);
         if (t + 2 < ntiles) stash_side(t + 2, e_nx2);
@@ -505,14 +529,21 @@ template <int D, int NW>
 __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW == 4 ? 2 : 1, 2))) attn_kernel(AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const DevicePlan& pl = a.plan;
-    const int item = xcd_contiguous_item(blockIdx.x, pl.nQB * a.BH);
-    if (item < 0) return;
+    // Workgroup ids go to the 8 XCDs round-robin.  Every XCD takes one eighth of a head's query
+    // blocks, a contiguous run of the pattern's block order (neighbours in that order walk nearly
+    // the same key tiles, which they then share through the XCD's L2), and all XCDs move through
+    // the heads together, so the K/V of the head in flight (tens of MB) stays resident in the
+    // memory-side cache for whatever misses L2.
+    const int per_xcd = (pl.nQB + 7) >> 3;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int ordinal = xcd * per_xcd + slot % per_xcd;
+    if (ordinal >= pl.nQB) return;
     QueryBlock qk;
-    qk.bh = item / pl.nQB;
-    qk.qb = item % pl.nQB;
+    qk.bh = slot / per_xcd;
     int cls = a.head_class[qk.bh];
     if (static_cast<unsigned>(cls) > 3u) cls = RF_DENSE;
     qk.cls = cls;
+    qk.qb = cls == RF_DENSE ? ordinal : pl.qorder[cls][ordinal];
     qk.cols = nullptr;
     if (cls == RF_DENSE) {
         qk.ntiles = pl.nKT;
@@ -543,8 +574,7 @@ static int launch_one(const AttnArgs& a, hipStream_t st) {
         if (e != hipSuccess) return static_cast<int>(e);
         configured = true;
     }
-    const int total = a.plan.nQB * a.BH;
-    const int grid = 8 * ((total + 7) / 8);
+    const int grid = 8 * ((a.plan.nQB + 7) / 8) * a.BH;
     hipLaunchKernelGGL((attn_kernel<D, NW>), dim3(grid), dim3(NT), smem, st, a);
     return static_cast<int>(hipGetLastError());
 }

@@ -36,6 +36,7 @@ struct HostPlan {
     int first_text_qb;  // first query block holding a text row (nQB if there is none)
     // CSR lists of key tiles per query block; Textural: text-holding query blocks only
     std::vector<int32_t> row_ptr[3], cols[3];
+    std::vector<int32_t> qorder[3];  // order in which a head's query blocks are handed out (a permutation)
     std::vector<int32_t> attr[3];  // per token: frame index / in-frame index / 0 if kept by Eq. 4 else 1
     std::vector<int32_t> cidx;     // compacted position -> token index (Textural)
 };
@@ -54,6 +55,7 @@ struct DevicePlan {
     const int32_t* row_ptr[3];
     const int32_t* cols[3];
     const int32_t* attr[3];
+    const int32_t* qorder[3];
     const int32_t* cidx;
     int radius[3];
     int N, Nv, Nc;

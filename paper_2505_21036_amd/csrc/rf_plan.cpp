@@ -62,6 +62,71 @@ inline int span_reach(Span a, Span b) { return std::max(b.hi - a.lo, a.hi - b.lo
 
 }  // namespace
 
+// Order in which a head's query blocks are handed to workgroups (the kernel gives XCD x the
+// ordinals [x * ceil(nQB/8), (x+1) * ceil(nQB/8)) of this order, and all XCDs advance together).
+// Two aims: blocks that run at the same time should walk the same key tiles, and the eight
+// shares should hold equal work.  Blocks are first put in a locality order (token order; under
+// the Temporal pattern, whose lists depend only on the in-frame position, grouped by position
+// across frames), cut into short runs, and the runs are dealt longest-first to the share with
+// the least work that still has room.
+static void order_query_blocks(HostPlan* plan) {
+    HostPlan& P = *plan;
+    const int nQB = P.nQB, block = P.block, HW = P.g.HW, Nv = P.g.Nv;
+    const int per_share = (nQB + 7) / 8;
+    constexpr int kRunBlocks = 8;
+    for (int cls = 0; cls < 3; ++cls) {
+        std::vector<int32_t> ord(nQB);
+        for (int qb = 0; qb < nQB; ++qb) ord[qb] = qb;
+        if (cls == RF_TEMPORAL) {
+            auto key = [&](int qb) {
+                const int64_t q0 = static_cast<int64_t>(qb) * block;
+                return q0 < Nv ? (q0 % HW) / block : (HW / block + 1);  // blocks that start in the text go last
+            };
+            std::stable_sort(ord.begin(), ord.end(), [&](int a, int b) { return key(a) < key(b); });
+        }
+        auto work = [&](int qb) -> int64_t {
+            if (cls == RF_TEXTURAL && qb < P.first_text_qb) return P.nCT;
+            return P.row_ptr[cls][qb + 1] - P.row_ptr[cls][qb];
+        };
+        struct Run { int first, len; int64_t work; };
+        std::vector<Run> runs;
+        for (int i = 0; i < nQB; i += kRunBlocks) {
+            Run r{i, std::min(kRunBlocks, nQB - i), 0};
+            for (int j = 0; j < r.len; ++j) r.work += work(ord[i + j]);
+            runs.push_back(r);
+        }
+        std::vector<int> by_work(runs.size());
+        for (size_t i = 0; i < runs.size(); ++i) by_work[i] = static_cast<int>(i);
+        std::stable_sort(by_work.begin(), by_work.end(), [&](int a, int b) { return runs[a].work > runs[b].work; });
+        std::vector<std::vector<int>> share(8);  // run indices per share
+        int64_t load[8] = {0};
+        int room[8];
+        for (int x = 0; x < 8; ++x) room[x] = std::max(0, std::min(per_share, nQB - x * per_share));
+        std::vector<int32_t> leftovers;  // blocks of runs that had to be split
+        for (int ri : by_work) {
+            int best = -1;
+            for (int x = 0; x < 8; ++x)
+                if (room[x] >= runs[ri].len && (best < 0 || load[x] < load[best])) best = x;
+            if (best < 0) {
+                for (int j = 0; j < runs[ri].len; ++j) leftovers.push_back(ord[runs[ri].first + j]);
+                continue;
+            }
+            share[best].push_back(ri);
+            load[best] += runs[ri].work;
+            room[best] -= runs[ri].len;
+        }
+        std::vector<int32_t>& out = P.qorder[cls];
+        out.clear();
+        size_t lo = 0;
+        for (int x = 0; x < 8; ++x) {
+            std::sort(share[x].begin(), share[x].end());  // keep neighbouring runs next to each other
+            for (int ri : share[x])
+                for (int j = 0; j < runs[ri].len; ++j) out.push_back(ord[runs[ri].first + j]);
+            for (; room[x] > 0 && lo < leftovers.size(); --room[x]) out.push_back(leftovers[lo++]);
+        }
+    }
+}
+
 void build_plan(const Geometry& g, int block, HostPlan* plan) {
     HostPlan& P = *plan;
     P.g = g;
@@ -136,6 +201,7 @@ void build_plan(const Geometry& g, int block, HostPlan* plan) {
             rp[qb + 1] = static_cast<int32_t>(co.size());
         }
     }
+    order_query_blocks(plan);
 }
 
 void flatten_class(const HostPlan& P, int cls, std::vector<int32_t>* row_ptr, std::vector<int32_t>* cols) {

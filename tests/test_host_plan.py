@@ -90,6 +90,29 @@ def test_textural_lists(lay, tau, block):
             assert (partial == ~full[qb, kbs]).all()
 
 
+@pytest.mark.parametrize("lay", LAYOUTS + [(33, 45, 80, 256), (13, 30, 45, 226)])
+@pytest.mark.parametrize("block", [64, 128])
+def test_query_block_order_is_a_permutation(lay, block):
+    rl = rf.rf_layout(*lay)
+    nqb = -(-(lay[0] * lay[1] * lay[2] + lay[3]) // block)
+    for cls in (rf.RF_SPATIAL, rf.RF_TEMPORAL, rf.RF_TEXTURAL, rf.RF_DENSE):
+        order = rf.rf_plan_order(rl, None, block, cls)
+        assert sorted(order.tolist()) == list(range(nqb))
+    assert (rf.rf_plan_order(rl, None, block, rf.RF_DENSE) == np.arange(nqb)).all()
+
+
+def test_query_block_order_balances_the_eight_shares():
+    """At the 720p shape each XCD's share of a head carries about the same number of key tiles."""
+    rl = rf.rf_layout(33, 45, 80, 256)
+    for cls in (rf.RF_SPATIAL, rf.RF_TEMPORAL):
+        row_ptr, _ = rf.rf_plan_host(rl, None, 128, cls)
+        work = np.diff(row_ptr)
+        order = rf.rf_plan_order(rl, None, 128, cls)
+        per = -(-len(order) // 8)
+        loads = [work[order[x * per:(x + 1) * per]].sum() for x in range(8)]
+        assert max(loads) <= 1.03 * (sum(loads) / 8), loads
+
+
 def test_paper_shapes_executed_fractions():
     """At the 720p shape with block 128 about half of the (block, tile) pairs are visited per pattern."""
     rl = rf.rf_layout(33, 45, 80, 256)
