@@ -21,6 +21,12 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 
+# HBM-side bytes of one attention launch of the timed step (ARM-chosen classes), from the rocprofv3
+# --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/attn_kernel_hunyuan720p.md: counter
+# values in KiB, FETCH_SIZE scaled x2.0 and WRITE_SIZE x1.0 (what the same counters read for a
+# 1 GiB device copy).  Only known for the workload / block it was profiled on.
+MEASURED_TRAFFIC_BYTES = {("hunyuan720p", 128): (2.0 * 6.848e7 + 1.0 * 7.143e5) * 1024}
+
 
 def kept_pairs(cls, w, bw_s=0.25, bw_t=0.25, tau=2):
     """Token pairs (query, key) one head keeps under a pattern: bookkeeping for FLOP counts."""
@@ -50,7 +56,7 @@ def main():
     ap.add_argument("--workload", default="hunyuan720p")
     ap.add_argument("--block", type=int, default=0, help="skip-list block (64|128); 0 = the workload's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", default="", help="profiling aid: run just 'step', 'arm', 'thirds', 'dense', or every head 'spatial' / 'temporal' / 'textural'")
+    ap.add_argument("--only", default="", help="profiling aid: run just 'step', 'arm', 'thirds', 'dense', every head 'spatial' / 'temporal' / 'textural', or 'copy' (a 1 GiB device copy)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
@@ -98,7 +104,10 @@ def main():
     if args.only:
         one = {n: torch.full((w.B, w.nH), c, dtype=torch.int32, device=dev)
                for n, c in (("spatial", rf.RF_SPATIAL), ("temporal", rf.RF_TEMPORAL), ("textural", rf.RF_TEXTURAL))}
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev) if args.only == "copy" else None
+        dst = torch.empty_like(src) if src is not None else None
         fn = {"step": step, "arm": arm, "thirds": lambda: attn(thirds), "dense": lambda: attn(dense),
+              "copy": lambda: dst.copy_(src),  # 1 GiB read + 1 GiB written: calibrates FETCH_SIZE / WRITE_SIZE
               "spatial": lambda: attn(one["spatial"]), "temporal": lambda: attn(one["temporal"]),
               "textural": lambda: attn(one["textural"])}[args.only]
         arm()
@@ -185,7 +194,7 @@ def main():
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(useful_arm / ms_attn_arm_classes / 1e9 / PEAK_BF16_TFLOPS, 4),
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, block)),
         },
         "detail": {
             "attention_ms_arm_classes": round(ms_attn_arm_classes, 4),

@@ -525,8 +525,13 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
     }
 }
 
+// Wavefronts per SIMD the register allocation is held to: three for head_dim 64 (measured
+// best; its accumulators are half the size), two for 96 and 128, one for the 64-row blocks of
+// the larger head dims, whose two-unit staging would otherwise spill.
+constexpr int attn_waves_per_simd(int D, int NW) { return NW == 4 ? (D == 64 ? 3 : 2) : (D == 64 ? 2 : 1); }
+
 template <int D, int NW>
-__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW == 4 ? 2 : 1, 2))) attn_kernel(AttnArgs a) {
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(attn_waves_per_simd(D, NW), attn_waves_per_simd(D, NW)))) attn_kernel(AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const DevicePlan& pl = a.plan;
     // Workgroup ids go to the 8 XCDs round-robin.  Every XCD takes one eighth of a head's query
