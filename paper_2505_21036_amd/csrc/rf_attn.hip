@@ -17,31 +17,52 @@ enum : int {
     MODE_LISTED = 2    // the CSR list of the head's pattern; partial tiles re-apply the predicate
 };
 
-// Two ways of getting a 64-key tile of K and V from global memory into LDS and of reading
-// MFMA operands back out.  Both expose: init(), issue(), commit(), k_frag(), v_frag().
-
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-// (1) DirectTile, head_dim 64 and 128: global_load_lds writes the tile straight into LDS (no
-// staging registers).  A wavefront instruction fills 1 KiB of consecutive LDS, lane l bytes
-// 16*l .. 16*l+15, so rows are unpadded; bank conflicts are avoided by permuting, per row, which
-// 16-byte chunk of the row a slot holds (slot position = chunk ^ X(row)), which costs nothing
-// because every lane chooses its own global address.  K is read back 16 bytes per lane as the A
-// operand of S^T = K Q^T; V stays row-major [key][channel] and ds_read_b64_tr_b16 transposes it
-// on the way out into the A operand of O^T = V^T P^T (8 consecutive keys of one channel per lane).
+// A 64-key tile of K and of V in LDS, filled by global_load_lds (global -> LDS without staging
+// registers) and read back as MFMA operands.
+//
+// A wavefront load instruction fills 1 KiB of consecutive LDS, lane l bytes 16*l .. 16*l+15, so
+// rows are unpadded; bank conflicts are avoided by permuting, per row, which 16-byte chunk of the
+// row a slot holds, which costs nothing because every lane chooses its own global address.  K is
+// read back 16 bytes per lane as the A operand of S^T = K Q^T; V stays row-major [key][channel]
+// and ds_read_b64_tr_b16 transposes it on the way out into the A operand of O^T = V^T P^T
+// (8 consecutive keys of one channel per lane).
+//
+// Chunk permutations (chunk = 16 bytes = 8 channels; a row has CH = D/8 of them):
+//   K: the 16 lanes of a read phase take one chunk index from 16 different rows; they must hit 16
+//      different 16-byte bank groups.  head_dim 128 / 64: slot = chunk ^ X(row), X = row % 16, resp.
+//      (row / 2) % 8.  head_dim 96 (12 chunks, rows start 48 banks apart): slot = (chunk + (row/4) % 4) mod 12.
+//   V: the 32 lanes of a transposing read phase take one 64-byte block from 4 consecutive rows;
+//      head_dim 128 / 64: slot = chunk ^ 4*(row % 4), resp. ^ 4*((row/2) % 2); head_dim 96 needs
+//      none, its 192-byte rows already rotate through the four 64-byte bank groups.
 template <int D, int NW>
 struct DirectTile {
-    static_assert(D == 64 || D == 128, "row length must be a power of two number of 16-byte chunks");
+    static_assert(D == 64 || D == 96 || D == 128, "unsupported head_dim");
+    static constexpr bool POW2 = D != 96;
     static constexpr int NT = 64 * NW, CH = D / 8, ROW = 2 * D;
     static constexpr int K_BYTES = kTileK * ROW, V_BYTES = kTileK * ROW;
     static constexpr int SEGS = kTileK * CH / 64;  // 1 KiB segments per tile
     static constexpr int V_READS_PER_FRAG = 2;
     static constexpr int PER_WAVE = SEGS / NW;     // load instructions per tensor per thread
+    static_assert(SEGS % NW == 0, "segments must divide evenly among the wavefronts");
 
-    // chunk permutation of a row: K spreads the 16 rows a read phase touches over all banks,
-    // V spreads the 4 rows a transposing read phase touches over the four 64-byte bank groups
-    static __device__ __forceinline__ int xk(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
-    static __device__ __forceinline__ int xv(int row) { return D == 128 ? 4 * (row & 3) : 4 * ((row >> 1) & 1); }
+    static __device__ __forceinline__ int k_slot(int row, int chunk) {
+        if (D == 128) return chunk ^ (row & 15);
+        if (D == 64) return chunk ^ ((row >> 1) & 7);
+        const int p = chunk + ((row >> 2) & 3);
+        return p >= CH ? p - CH : p;
+    }
+    static __device__ __forceinline__ int k_chunk(int row, int slot) {  // inverse of k_slot
+        if (POW2) return k_slot(row, slot);
+        const int ch = slot - ((row >> 2) & 3);
+        return ch < 0 ? ch + CH : ch;
+    }
+    static __device__ __forceinline__ int v_slot(int row, int chunk) {  // its own inverse
+        if (D == 128) return chunk ^ (4 * (row & 3));
+        if (D == 64) return chunk ^ (4 * ((row >> 1) & 1));
+        return chunk;
+    }
 
     static __device__ __forceinline__ uint32_t lds_offset(const unsigned char* p) {
         return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const unsigned char*)p));
@@ -54,33 +75,38 @@ struct DirectTile {
     }
 
     int wave, lane;
-    int k_base;          // byte offset of this lane's K operand for kb2 = 0, c = 0
+    int k_base;          // byte offset of this lane's K operand for kb2 = 0 (chunk 0 of its row when !POW2)
+    int k_rot;           // !POW2: hf + rotation of this lane's K row
     int v_base[D / 32];  // byte offset of this lane's V operand for u = 0, first half, per channel block
-    static constexpr int ROWS_PER_LOAD = 64 * NW / CH;  // tile rows between a thread's successive loads
-    // X(row) has period 16 for K and 4 for V, so V's lane offset never depends on the load index j
-    // and K's only when a load covers fewer than 16 rows
-    static constexpr int K_VARIANTS = (ROWS_PER_LOAD % 16 == 0) ? 1 : PER_WAVE;
-    static_assert(ROWS_PER_LOAD % 4 == 0, "V row permutation must not change between loads");
-    uint32_t k_lane_off[K_VARIANTS], v_lane_off;  // global byte offsets of this lane's slot within a load
+    // Loads of a tile of consecutive tokens: load j of a lane reads  base + j*STEP + lane_off[j].
+    // With power-of-two rows a lane keeps its slot position and moves down ROWS_PER_LOAD rows per
+    // load, and the permutations have period 16 (K) and 4 (V) rows, so one offset serves every j
+    // (K: only if a load covers a multiple of 16 rows); 12-chunk rows need an offset per load.
+    static constexpr int ROWS_PER_LOAD = 64 * NW / CH;
+    static constexpr int STEP = POW2 ? ROWS_PER_LOAD * ROW : 0;
+    static constexpr int K_VARIANTS = (POW2 && ROWS_PER_LOAD % 16 == 0) ? 1 : PER_WAVE;
+    static constexpr int V_VARIANTS = POW2 ? 1 : PER_WAVE;
+    static_assert(!POW2 || ROWS_PER_LOAD % 4 == 0, "V row permutation must not change between loads");
+    uint32_t k_lane_off[K_VARIANTS], v_lane_off[V_VARIANTS];
 
     __device__ __forceinline__ void init(int tid) {
         lane = tid & 63;
         wave = __builtin_amdgcn_readfirstlane(tid >> 6);
         const int hf = lane >> 5, m = lane & 31, g4 = lane >> 4, i = lane & 15;
-        const int krow = key_of_mfma_row(m);
-        k_base = krow * ROW + 16 * (hf ^ xk(krow));
-        {
-            // slot of load j: tile row  j*ROWS_PER_LOAD + row0, position pos; X(row) is the same for all j
-            const int slot = wave * 64 + lane, row0 = slot / CH, pos = slot % CH;
+        const int krow = key_of_mfma_row(m);  // + 32*kb2: invisible to the K permutation
+        k_base = POW2 ? krow * ROW + 16 * k_slot(krow, hf) : krow * ROW;
+        k_rot = hf + ((krow >> 2) & 3);
 #pragma unroll
-            for (int j = 0; j < K_VARIANTS; ++j) k_lane_off[j] = row0 * ROW + 16 * (pos ^ xk(row0 + j * ROWS_PER_LOAD));
-            v_lane_off = row0 * ROW + 16 * (pos ^ xv(row0));
+        for (int j = 0; j < PER_WAVE; ++j) {
+            const int slot = (j * NW + wave) * 64 + lane, row = slot / CH, pos = slot % CH;
+            if (j < K_VARIANTS) k_lane_off[j] = row * ROW + 16 * k_chunk(row, pos) - j * STEP;
+            if (j < V_VARIANTS) v_lane_off[j] = row * ROW + 16 * v_slot(row, pos) - j * STEP;
         }
-        const int vrow = 8 * hf + (i >> 2);  // + 16*u + 4*half: multiples of 4, invisible to xv()
+        const int vrow = 8 * hf + (i >> 2);  // + 16*u + 4*half: multiples of 4, invisible to the V permutation
 #pragma unroll
         for (int db = 0; db < D / 32; ++db) {
             const int chunk = 4 * db + 2 * (g4 & 1) + ((i & 3) >> 1);
-            v_base[db] = vrow * ROW + 16 * (chunk ^ xv(vrow)) + 8 * (i & 1);
+            v_base[db] = vrow * ROW + 16 * v_slot(vrow, chunk) + 8 * (i & 1);
         }
     }
 
@@ -93,27 +119,35 @@ struct DirectTile {
             const int seg = j * NW + wave;
             const int slot = seg * 64 + lane, row = slot / CH, pos = slot % CH;
             const uint32_t row_off = static_cast<uint32_t>(tok(row)) * ROW;
-            const uint32_t k_off = row_off + 16u * (pos ^ xk(row)), v_off = row_off + 16u * (pos ^ xv(row));
-            dma16(kh, k_off, lds_offset(kl) + seg * 1024);
-            dma16(vh, v_off, lds_offset(vl) + seg * 1024);
+            dma16(kh, row_off + 16u * k_chunk(row, pos), lds_offset(kl) + seg * 1024);
+            dma16(vh, row_off + 16u * v_slot(row, pos), lds_offset(vl) + seg * 1024);
         }
     }
-    // same for a tile of 64 consecutive tokens starting at kh / vh: only uniform bases move
+    // same for a tile of 64 consecutive tokens starting at kh / vh
     __device__ __forceinline__ void issue_consecutive(const unsigned char* kh, const unsigned char* vh, unsigned char* kl,
                                                       unsigned char* vl) {
 #pragma unroll
         for (int j = 0; j < PER_WAVE; ++j) {
             const int seg = j * NW + wave;
-            dma16(kh + j * ROWS_PER_LOAD * ROW, k_lane_off[j % K_VARIANTS], lds_offset(kl) + seg * 1024);
-            dma16(vh + j * ROWS_PER_LOAD * ROW, v_lane_off, lds_offset(vl) + seg * 1024);
+            dma16(kh + j * STEP, k_lane_off[j % K_VARIANTS], lds_offset(kl) + seg * 1024);
+            dma16(vh + j * STEP, v_lane_off[j % V_VARIANTS], lds_offset(vl) + seg * 1024);
         }
     }
     // the tile is in LDS once this thread's loads have landed (the barrier that follows publishes it)
     __device__ __forceinline__ void commit(unsigned char*, unsigned char*) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+    // A operand of S^T = K Q^T: keys 32*kb2 .. +31 (permuted per lane), channels 16*c + 8*hf .. +7
     __device__ __forceinline__ bf16x8 k_frag(const unsigned char* kl, int kb2, int c) const {
-        return as_bf16x8(*reinterpret_cast<const u32x4*>(kl + ((k_base ^ (32 * c)) + kb2 * 32 * ROW)));
+        int off;
+        if (POW2) {
+            off = k_base ^ (32 * c);  // chunk 2c + hf: the permutation is an XOR, so c toggles address bits
+        } else {
+            const int p = 2 * c + k_rot;
+            off = k_base + 16 * (p >= CH ? p - CH : p);
+        }
+        return as_bf16x8(*reinterpret_cast<const u32x4*>(kl + off + kb2 * 32 * ROW));
     }
+    // A operand of O^T = V^T P^T: channels 32*db + lane%32, keys 16*u + 8*hf .. +7
     __device__ __forceinline__ bf16x8 v_frag(const unsigned char* vl, int db, int u) const {
         typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
         const unsigned char* p = vl + v_base[db] + 16 * u * ROW;
@@ -125,116 +159,9 @@ struct DirectTile {
     }
 };
 
-// (2) StagedTile, any head_dim (used for 96): global -> registers -> LDS.  K rows are padded by
-// 16 bytes; V is transposed in registers and stored one LDS row per channel.  A thread owns
-// "units": unit (kg, dc) covers keys 8*kg .. 8*kg+7; from V it loads channels 4*dc .. 4*dc+3 of
-// those rows (8 bytes each), from K four of the same rows, 16 bytes each.
-template <int D, int NW>
-struct StagedTile {
-    static constexpr int NT = 64 * NW;
-    static constexpr int K_ROW = 2 * D + 16;       // bytes; +16 pad: conflict-free 16-B reads down a column
-    static constexpr int V_ROW = 2 * kTileK + 16;  // bytes
-    static constexpr int K_BYTES = kTileK * K_ROW;
-    static constexpr int V_BYTES = D * V_ROW;
-    static constexpr int DC = D / 4;               // units per key group
-    static constexpr int V_READS_PER_FRAG = 1;
-    static constexpr int UNITS = (kTileK / 8) * DC;
-    static constexpr int PER_THREAD = (UNITS + NT - 1) / NT;
-    static constexpr bool EXACT = UNITS % NT == 0;
-
-    int tid, hf, m;
-    u32x4 kreg[PER_THREAD][4];
-    u32x2 vreg[PER_THREAD][8];
-
-    __device__ __forceinline__ void init(int t) {
-        tid = t;
-        hf = (t & 63) >> 5;
-        m = t & 31;
-    }
-    static __device__ __forceinline__ int k_row_in_group(int dc) { return 4 * (dc / (D / 8)); }
-    static __device__ __forceinline__ int k_chunk(int dc) { return dc % (D / 8); }
-
-    template <typename F>
-    __device__ __forceinline__ void issue(const unsigned char* kh, const unsigned char* vh, unsigned char*,
-                                          unsigned char*, F tok) {
-#pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            const int u = tid + i * NT;
-            if (EXACT || u < UNITS) {
-                const int kg = u / DC, dc = u % DC;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const uint32_t row_off = static_cast<uint32_t>(tok(8 * kg + e)) * (2u * D);
-                    vreg[i][e] = *reinterpret_cast<const u32x2*>(vh + row_off + 8u * dc);
-                }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t row_off = static_cast<uint32_t>(tok(8 * kg + k_row_in_group(dc) + j)) * (2u * D);
-                    kreg[i][j] = *reinterpret_cast<const u32x4*>(kh + row_off + 16u * k_chunk(dc));
-                }
-            }
-        }
-    }
-
-    __device__ __forceinline__ void issue_consecutive(const unsigned char* kh, const unsigned char* vh, unsigned char* kl,
-                                                      unsigned char* vl) {
-        issue(kh, vh, kl, vl, [](int row) { return row; });
-    }
-
-    __device__ __forceinline__ void commit(unsigned char* kl, unsigned char* vl) {
-#pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            const int u = tid + i * NT;
-            if (EXACT || u < UNITS) {
-                const int kg = u / DC, dc = u % DC;
-                const int r0 = 8 * kg + k_row_in_group(dc);
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    *reinterpret_cast<u32x4*>(kl + (r0 + j) * K_ROW + 16 * k_chunk(dc)) = kreg[i][j];
-                uint32_t o[4][4];  // [channel][key pair]
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {  // keys 2w, 2w+1 side by side, one channel per output row
-                    const u32x2 a = vreg[i][2 * w], b = vreg[i][2 * w + 1];
-                    o[0][w] = __builtin_amdgcn_perm(b.x, a.x, 0x05040100u);
-                    o[1][w] = __builtin_amdgcn_perm(b.x, a.x, 0x07060302u);
-                    o[2][w] = __builtin_amdgcn_perm(b.y, a.y, 0x05040100u);
-                    o[3][w] = __builtin_amdgcn_perm(b.y, a.y, 0x07060302u);
-                }
-                // 16-byte key chunk kg of channel row d sits at chunk position kg ^ ((d >> 4) & 3):
-                // with the 36-dword row pitch this spreads the 16 lanes of a write phase over all banks
-                const int pos = kg ^ ((dc >> 2) & 3);
-#pragma unroll
-                for (int dd = 0; dd < 4; ++dd)
-                    *reinterpret_cast<u32x4*>(vl + (4 * dc + dd) * V_ROW + 16 * pos) =
-                        u32x4{o[dd][0], o[dd][1], o[dd][2], o[dd][3]};
-            }
-        }
-    }
-
-    // A operand of S^T = K Q^T: keys 32*kb2 .. +31 (permuted per lane), channels 16*c + 8*hf .. +7
-    __device__ __forceinline__ bf16x8 k_frag(const unsigned char* kl, int kb2, int c) const {
-        const int row = 32 * kb2 + key_of_mfma_row(m);
-        return as_bf16x8(*reinterpret_cast<const u32x4*>(kl + row * K_ROW + 32 * c + 16 * hf));
-    }
-    // A operand of O^T = V^T P^T: channels 32*db + m, keys 16*u + 8*hf .. +7
-    __device__ __forceinline__ bf16x8 v_frag(const unsigned char* vl, int db, int u) const {
-        const int row = 32 * db + m;
-        const int pos = (2 * u + hf) ^ ((row >> 4) & 3);
-        return as_bf16x8(*reinterpret_cast<const u32x4*>(vl + row * V_ROW + 16 * pos));
-    }
-};
-
 template <int D, int NW>
 struct TileFor {
-    using type = StagedTile<D, NW>;
-};
-template <int NW>
-struct TileFor<64, NW> {
-    using type = DirectTile<64, NW>;
-};
-template <int NW>
-struct TileFor<128, NW> {
-    using type = DirectTile<128, NW>;
+    using type = DirectTile<D, NW>;
 };
 
 template <int D, int NW>
@@ -525,10 +452,9 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
     }
 }
 
-// Wavefronts per SIMD the register allocation is held to: three for head_dim 64 (measured
-// best; its accumulators are half the size), two for 96 and 128, one for the 64-row blocks of
-// the larger head dims, whose two-unit staging would otherwise spill.
-constexpr int attn_waves_per_simd(int D, int NW) { return NW == 4 ? (D == 64 ? 3 : 2) : (D == 64 ? 2 : 1); }
+// Wavefronts per SIMD the register allocation is held to: three for head_dim 64 with 128-row
+// blocks (measured best; its accumulators are half the size), two otherwise.
+constexpr int attn_waves_per_simd(int D, int NW) { return (D == 64 && NW == 4) ? 3 : 2; }
 
 template <int D, int NW>
 __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(attn_waves_per_simd(D, NW), attn_waves_per_simd(D, NW)))) attn_kernel(AttnArgs a) {
