@@ -76,6 +76,7 @@ def main():
     hc = torch.empty(w.B, w.nH, dtype=torch.int32, device=dev)
     rec = torch.empty(w.B, w.nH, 2, dtype=torch.float32, device=dev)
     ws = torch.empty(max(rf.rf_arm_workspace_bytes(w.B, w.nH, rl), 4), dtype=torch.uint8, device=dev)
+    ws_attn = torch.empty(rf.rf_attention_workspace_bytes(w.B, w.nH, w.D, rl), dtype=torch.uint8, device=dev)
     thirds = inp.thirds_classes(w).to(dev)
     dense = torch.full((w.B, w.nH), rf.RF_DENSE, dtype=torch.int32, device=dev)
 
@@ -83,7 +84,7 @@ def main():
         rf.rf_arm_classify(Q, K, rl, None, rf.RF_SAMPLE_FIRST_FRAME, 0.9, hc, rec, ws)
 
     def attn(classes):
-        rf.rf_sparse_attention(Q, K, V, classes, rl, None, block, O)
+        rf.rf_sparse_attention(Q, K, V, classes, rl, None, block, O, ws_attn)
 
     def step():
         arm()

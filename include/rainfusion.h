@@ -57,7 +57,7 @@ enum rf_status {
     RF_ERR_PARAM = -4,     /* bandwidth outside [0, 1], tex_stride < 1, sample_interval < 0, bad sample_mode,
                               threshold not in [0, 1] or NaN */
     RF_ERR_BLOCK = -5,     /* block not 64 or 128 */
-    RF_ERR_WORKSPACE = -6, /* workspace NULL or smaller than rf_arm_workspace_bytes() */
+    RF_ERR_WORKSPACE = -6, /* a required workspace is NULL, or a workspace is too small or misaligned */
     RF_ERR_HIP = -7        /* a HIP runtime call failed (allocation, copy or launch) */
 };
 
@@ -95,10 +95,19 @@ size_t rf_arm_workspace_bytes(int B, int nH, const rf_layout *layout, const rf_p
  *               output of rf_arm_classify can be passed on without a host round trip.
  *               Values outside 0..3 are treated as RF_DENSE.
  * O           : device, bf16 [B, nH, N, D], written.
+ * workspace   : optional device scratch of at least rf_attention_workspace_bytes() bytes, 16-byte
+ *               aligned.  If given, the kept keys and values of every Textural head are first packed
+ *               into it (K_C, V_C of Eq. 5 made contiguous), which is faster than the default of
+ *               gathering their rows through an index table; the result is the same.  NULL: no
+ *               packing.  Contents undefined afterwards; overlapping calls need separate workspaces.
  */
 int rf_sparse_attention(const void *Q, const void *K, const void *V, const int32_t *head_class, int B,
                         int nH, int D, const rf_layout *layout, const rf_params *params, int block,
-                        void *O, void *stream);
+                        void *O, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of the optional workspace of rf_sparse_attention (room for K_C and V_C of every head);
+ * 0 if the arguments are invalid. */
+size_t rf_attention_workspace_bytes(int B, int nH, int D, const rf_layout *layout, const rf_params *params);
 
 /*
  * Host-side view of the list rf_sparse_attention walks (Fig. 2a "applying the sparse

@@ -63,7 +63,10 @@ def load_library():
     lib.rf_arm_classify.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, PL, PP, C.c_int, C.c_float, vp, vp, vp,
                                     C.c_size_t, vp]
     lib.rf_sparse_attention.restype = C.c_int
-    lib.rf_sparse_attention.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, PL, PP, C.c_int, vp, vp]
+    lib.rf_sparse_attention.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, PL, PP, C.c_int, vp, vp, C.c_size_t,
+                                        vp]
+    lib.rf_attention_workspace_bytes.restype = C.c_size_t
+    lib.rf_attention_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, PL, PP]
     lib.rf_plan_host.restype = C.c_int
     lib.rf_plan_host.argtypes = [PL, PP, C.c_int, C.c_int, vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
     lib.rf_plan_order.restype = C.c_int
@@ -128,8 +131,13 @@ def rf_arm_classify(Q, K, layout, params=None, sample_mode=RF_SAMPLE_FIRST_FRAME
     return head_class, recalls
 
 
-def rf_sparse_attention(Q, K, V, head_class, layout, params=None, block=128, out=None):
-    """Sparse attention forward (Eq. 1-5). head_class: int32 device tensor [B, nH]. Returns O."""
+def rf_attention_workspace_bytes(B, nH, D, layout, params=None):
+    return load_library().rf_attention_workspace_bytes(B, nH, D, C.byref(layout), _pp(params))
+
+
+def rf_sparse_attention(Q, K, V, head_class, layout, params=None, block=128, out=None, workspace=None):
+    """Sparse attention forward (Eq. 1-5). head_class: int32 device tensor [B, nH]. Returns O.
+    workspace: optional uint8 device tensor of rf_attention_workspace_bytes() bytes (packs K_C, V_C)."""
     import torch
     _check_bf16(Q, "Q")
     _check_bf16(K, "K", Q.shape)
@@ -144,8 +152,11 @@ def rf_sparse_attention(Q, K, V, head_class, layout, params=None, block=128, out
         out = torch.empty_like(Q)
     else:
         _check_bf16(out, "out", Q.shape)
+    ws_ptr, ws_bytes = (None, 0) if workspace is None else (workspace.data_ptr(),
+                                                           workspace.numel() * workspace.element_size())
     st = load_library().rf_sparse_attention(Q.data_ptr(), K.data_ptr(), V.data_ptr(), head_class.data_ptr(), B, nH,
-                                            D, C.byref(layout), _pp(params), block, out.data_ptr(), _stream())
+                                            D, C.byref(layout), _pp(params), block, out.data_ptr(), ws_ptr, ws_bytes,
+                                            _stream())
     if st != 0:
         raise RfError(st, "rf_sparse_attention")
     return out

@@ -213,9 +213,22 @@ int rf_arm_classify(const void* Q, const void* K, int B, int nH, int D, const rf
     return launch_arm(a, D, stream) == 0 ? RF_OK : RF_ERR_HIP;
 }
 
+static size_t packed_count(const Geometry& g) {
+    int64_t kept = 0;
+    for (int y = 0; y < g.H; ++y)
+        for (int x = 0; x < g.W; ++x) kept += ((y - x) % g.tau) == 0;
+    return static_cast<size_t>(kept * g.T + g.text_len);
+}
+
+size_t rf_attention_workspace_bytes(int B, int nH, int D, const rf_layout* layout, const rf_params* params) {
+    Geometry g;
+    if (resolve_geometry(layout, params, &g) != RF_OK || check_shape(B, nH, D, g) != RF_OK) return 0;
+    return 2 * static_cast<size_t>(B) * nH * packed_count(g) * D * sizeof(uint16_t);
+}
+
 int rf_sparse_attention(const void* Q, const void* K, const void* V, const int32_t* head_class, int B, int nH,
                         int D, const rf_layout* layout, const rf_params* params, int block, void* O,
-                        void* stream) {
+                        void* workspace, size_t workspace_bytes, void* stream) {
     if (!Q || !K || !V || !O || !head_class || !layout) return RF_ERR_NULL;
     Geometry g;
     int st = resolve_geometry(layout, params, &g);
@@ -223,6 +236,8 @@ int rf_sparse_attention(const void* Q, const void* K, const void* V, const int32
     st = check_shape(B, nH, D, g);
     if (st != RF_OK) return st;
     if (block != 64 && block != 128) return RF_ERR_BLOCK;
+    if (workspace && workspace_bytes < rf_attention_workspace_bytes(B, nH, D, layout, params)) return RF_ERR_WORKSPACE;
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 15)) return RF_ERR_WORKSPACE;
 
     const DevicePlan* dp = nullptr;
     st = get_attention_plan(g, block, &dp);
@@ -237,6 +252,11 @@ int rf_sparse_attention(const void* Q, const void* K, const void* V, const int32
     a.BH = B * nH;
     a.scale_log2 = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(D)));
     a.plan = *dp;
+    if (workspace) {
+        a.packed_k = static_cast<uint16_t*>(workspace);
+        a.packed_v = a.packed_k + static_cast<size_t>(B) * nH * dp->Nc * D;
+        if (launch_pack_textural(a, D, stream) != 0) return RF_ERR_HIP;
+    }
     return launch_attention(a, D, stream) == 0 ? RF_OK : RF_ERR_HIP;
 }
 

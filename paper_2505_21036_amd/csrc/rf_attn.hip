@@ -175,6 +175,8 @@ struct AttnSmem {
 
 struct QueryBlock {
     int bh, qb, cls;
+    const unsigned char* kbase;  // K and V rows of the key sequence walked (the head's, or its compacted copy)
+    const unsigned char* vbase;
     const int32_t* cols;  // MODE_LISTED: this query block's tile entries
     int ntiles;           // key tiles to visit
     int keyN;             // length of the key sequence walked (N, or Nc when compacted)
@@ -197,9 +199,8 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, 
     const int32_t* side_src = MODE == MODE_COMPACT ? pl.cidx : (MODE == MODE_LISTED ? pl.attr[qk.cls] : nullptr);
     int* side = reinterpret_cast<int*>(smem + SM::SIDE_OFF);
 
-    const size_t head_bytes = static_cast<size_t>(qk.bh) * N * D * 2;
-    const unsigned char* Kh = reinterpret_cast<const unsigned char*>(a.K) + head_bytes;
-    const unsigned char* Vh = reinterpret_cast<const unsigned char*>(a.V) + head_bytes;
+    const unsigned char* Kh = qk.kbase;
+    const unsigned char* Vh = qk.vbase;
     const uint16_t* Qh = a.Q + static_cast<size_t>(qk.bh) * N * D;
 
     // this lane's query
@@ -476,15 +477,27 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
     qk.cls = cls;
     qk.qb = cls == RF_DENSE ? ordinal : pl.qorder[cls][ordinal];
     qk.cols = nullptr;
+    const size_t head_bytes = static_cast<size_t>(qk.bh) * pl.N * D * 2;
+    qk.kbase = reinterpret_cast<const unsigned char*>(a.K) + head_bytes;
+    qk.vbase = reinterpret_cast<const unsigned char*>(a.V) + head_bytes;
     if (cls == RF_DENSE) {
         qk.ntiles = pl.nKT;
         qk.keyN = pl.N;
         attend<D, NW, MODE_ALL>(a, qk, smem);
     } else if (cls == RF_TEXTURAL && qk.qb < pl.first_text_qb) {
-        // Textural query blocks made only of video tokens see the compacted key sequence
+        // Textural query blocks made only of video tokens see the compacted key sequence (Eq. 5):
+        // as a packed copy made by pack_textural_kernel if the caller gave room for one, else
+        // gathered row by row through the index table
         qk.ntiles = pl.nCT;
         qk.keyN = pl.Nc;
-        attend<D, NW, MODE_COMPACT>(a, qk, smem);
+        if (a.packed_k) {
+            const size_t packed_bytes = static_cast<size_t>(qk.bh) * pl.Nc * D * 2;
+            qk.kbase = reinterpret_cast<const unsigned char*>(a.packed_k) + packed_bytes;
+            qk.vbase = reinterpret_cast<const unsigned char*>(a.packed_v) + packed_bytes;
+            attend<D, NW, MODE_ALL>(a, qk, smem);
+        } else {
+            attend<D, NW, MODE_COMPACT>(a, qk, smem);
+        }
     } else {
         const int e0 = pl.row_ptr[cls][qk.qb];
         qk.ntiles = pl.row_ptr[cls][qk.qb + 1] - e0;
@@ -492,6 +505,35 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
         qk.keyN = pl.N;
         attend<D, NW, MODE_LISTED>(a, qk, smem);
     }
+}
+
+// K_C, V_C of Eq. 5 made physical: for every Textural head, the kept keys' rows (then the text
+// rows) copied in order into the caller's workspace.  One workgroup per (64 packed rows, head).
+template <int D>
+__global__ void __launch_bounds__(256) pack_textural_kernel(AttnArgs a) {
+    const DevicePlan& pl = a.plan;
+    const int bh = blockIdx.y;
+    if (a.head_class[bh] != RF_TEXTURAL) return;
+    constexpr int CH = D / 8;  // 16-byte chunks per row
+    const size_t src_head = static_cast<size_t>(bh) * pl.N * D, dst_head = static_cast<size_t>(bh) * pl.Nc * D;
+    for (int i = threadIdx.x; i < kTileK * CH; i += 256) {
+        const int c = blockIdx.x * kTileK + i / CH, ch = i % CH;
+        if (c >= pl.Nc) break;
+        const size_t src = src_head + static_cast<size_t>(pl.cidx[c]) * D + 8 * ch;
+        const size_t dst = dst_head + static_cast<size_t>(c) * D + 8 * ch;
+        *reinterpret_cast<u32x4*>(a.packed_k + dst) = *reinterpret_cast<const u32x4*>(a.K + src);
+        *reinterpret_cast<u32x4*>(a.packed_v + dst) = *reinterpret_cast<const u32x4*>(a.V + src);
+    }
+}
+
+int launch_pack_textural(const AttnArgs& a, int D, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const dim3 grid(a.plan.nCT, a.BH);
+    if (D == 64) hipLaunchKernelGGL(pack_textural_kernel<64>, grid, dim3(256), 0, st, a);
+    else if (D == 96) hipLaunchKernelGGL(pack_textural_kernel<96>, grid, dim3(256), 0, st, a);
+    else if (D == 128) hipLaunchKernelGGL(pack_textural_kernel<128>, grid, dim3(256), 0, st, a);
+    else return static_cast<int>(hipErrorInvalidValue);
+    return static_cast<int>(hipGetLastError());
 }
 
 template <int D, int NW>

@@ -70,6 +70,9 @@ struct AttnArgs {
     const int32_t* head_class;
     int BH;            // B * nH
     float scale_log2;  // log2(e) / sqrt(D)
+    // optional: compacted K and V of Textural heads, [BH][Nc][D] each (null: gather through the index table)
+    uint16_t* packed_k;
+    uint16_t* packed_v;
     DevicePlan plan;
 };
 
@@ -97,6 +100,7 @@ struct ArmArgs {
 
 // Kernel launchers (defined in the .hip files). Return a hipError_t as int.
 int launch_attention(const AttnArgs& a, int D, void* stream);
+int launch_pack_textural(const AttnArgs& a, int D, void* stream);
 int launch_arm(const ArmArgs& a, int D, void* stream);
 
 }  // namespace rf

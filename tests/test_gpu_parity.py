@@ -47,10 +47,13 @@ def check(O_gpu_rows, O_ref, what):
     assert rel <= REL_L2, what
 
 
-def run_attention(w, Q, K, V, classes, block, params=None):
+def run_attention(w, Q, K, V, classes, block, params=None, packed=False):
     rl, _ = lay(w)
     hc = torch.as_tensor(classes, dtype=torch.int32).reshape(w.B, w.nH).to(DEV)
-    O = rf.rf_sparse_attention(Q, K, V, hc, rl, params, block)
+    ws = None
+    if packed:  # pack K_C, V_C of Textural heads into a caller-provided workspace first
+        ws = torch.empty(rf.rf_attention_workspace_bytes(w.B, w.nH, w.D, rl, params), dtype=torch.uint8, device=DEV)
+    O = rf.rf_sparse_attention(Q, K, V, hc, rl, params, block, workspace=ws)
     torch.cuda.synchronize()
     return O
 
@@ -67,13 +70,14 @@ def test_small_shapes_every_class_every_row(name, block, scale):
     rp, op = par()
     _, ol = lay(w)
     Q, K, V = inp.full_qkv(w, DEV, scale)
-    for cls in (rf.RF_SPATIAL, rf.RF_TEMPORAL, rf.RF_TEXTURAL, rf.RF_DENSE):
-        O = run_attention(w, Q, K, V, [cls] * (w.B * w.nH), block, rp)
+    for cls, packed in ((rf.RF_SPATIAL, False), (rf.RF_TEMPORAL, False), (rf.RF_TEXTURAL, False),
+                        (rf.RF_TEXTURAL, True), (rf.RF_DENSE, False)):
+        O = run_attention(w, Q, K, V, [cls] * (w.B * w.nH), block, rp, packed)
         for b in range(w.B):
             for h in range(w.nH):
                 q, k, v = (f32(t) for t in inp.head_qkv(w, b, h, scale))
                 ref = orc.attention(q, k, v, cls, ol, op)
-                check(O[b, h], ref, "%s blk%d scale%g cls%d head(%d,%d)" % (name, block, scale, cls, b, h))
+                check(O[b, h], ref, "%s blk%d scale%g cls%d packed%d head(%d,%d)" % (name, block, scale, cls, packed, b, h))
 
 
 def test_tiny_config_forced_classes():
@@ -96,13 +100,13 @@ def test_parameter_corners(bs, bt, tau):
     _, ol = lay(w)
     Q, K, V = inp.full_qkv(w, DEV, 6.0)
     classes = inp.round_robin_classes(w).flatten().tolist()
-    for block in (64, 128):
-        O = run_attention(w, Q, K, V, classes, block, rp)
+    for block, packed in ((64, False), (128, False), (128, True)):
+        O = run_attention(w, Q, K, V, classes, block, rp, packed)
         for b in range(w.B):
             for h in range(w.nH):
                 q, k, v = (f32(t) for t in inp.head_qkv(w, b, h, 6.0))
                 ref = orc.attention(q, k, v, classes[b * w.nH + h], ol, op)
-                check(O[b, h], ref, "corner bs%g bt%g tau%d blk%d head(%d,%d)" % (bs, bt, tau, block, b, h))
+                check(O[b, h], ref, "corner bs%g bt%g tau%d blk%d packed%d head(%d,%d)" % (bs, bt, tau, block, packed, b, h))
 
 
 @pytest.mark.parametrize("shape", [(1, 5, 5, 0), (1, 3, 3, 40), (2, 2, 2, 1), (3, 7, 9, 0)])
@@ -240,8 +244,10 @@ def test_hunyuan720p_headline_layer():
     classes = inp.thirds_classes(w).flatten().tolist()
     O = run_attention(w, Q, K, V, classes, w.block)
     sampled_parity(w, O, classes, [(0, 0), (0, 8), (0, 16)], 20, tag="thirds")
+    O = run_attention(w, Q, K, V, hc.flatten().tolist(), w.block, packed=True)  # as bench.py runs it
+    sampled_parity(w, O, hc.flatten().tolist(), [(0, 5)], 12, tag="arm-chosen, packed")
     O = run_attention(w, Q, K, V, hc.flatten().tolist(), w.block)
-    sampled_parity(w, O, hc.flatten().tolist(), [(0, 5)], 12, tag="arm-chosen")
+    sampled_parity(w, O, hc.flatten().tolist(), [(0, 6)], 12, tag="arm-chosen, gathered")
     # property at full size: constant values must come back as that constant on every row
     O = run_attention(w, Q, K, torch.ones_like(V), classes, w.block)
     assert (O.float() - 1).abs().max().item() <= 1e-2

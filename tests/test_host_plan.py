@@ -129,6 +129,7 @@ def test_every_declared_symbol_is_exported():
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = re.findall(r"\b(rf_[a-z_]+)\s*\(", hdr)
     assert set(names) >= {"rf_arm_classify", "rf_sparse_attention", "rf_arm_workspace_bytes", "rf_plan_host",
+                          "rf_attention_workspace_bytes", "rf_plan_order",
                           "rf_plan_clear", "rf_status_string", "rf_version"}
     for n in set(names):
         assert getattr(lib, n) is not None
@@ -142,9 +143,9 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     one = C.c_void_p(16)  # non-null dummy; never dereferenced because validation fails first
     ok_p = rf.rf_params.default()
 
-    def attn(Q=one, K=one, V=one, hc=one, B=1, nH=2, D=64, lay=L, par=ok_p, block=64, O=one):
+    def attn(Q=one, K=one, V=one, hc=one, B=1, nH=2, D=64, lay=L, par=ok_p, block=64, O=one, ws=None, wsb=0):
         return lib.rf_sparse_attention(Q, K, V, hc, B, nH, D, C.byref(lay) if lay else None,
-                                       C.byref(par) if par else None, block, O, None)
+                                       C.byref(par) if par else None, block, O, ws, wsb, None)
 
     assert attn(Q=None) == -1 and attn(O=None) == -1 and attn(hc=None) == -1 and attn(lay=None) == -1
     assert attn(D=80) == -2 and attn(B=0) == -2 and attn(nH=-1) == -2
@@ -153,6 +154,10 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     assert attn(par=rf.rf_params(1.5, 0.25, 2, 0)) == -4 and attn(par=rf.rf_params(0.25, -0.1, 2, 0)) == -4
     assert attn(par=rf.rf_params(0.25, 0.25, 0, 0)) == -4 and attn(par=rf.rf_params(float("nan"), 0.25, 2, 0)) == -4
     assert attn(block=32) == -5 and attn(block=256) == -5
+    need = rf.rf_attention_workspace_bytes(1, 2, 64, L)
+    assert need == 2 * 2 * 128 * 64 * 2  # half of the 256 tokens kept, K and V, 2 heads, bf16
+    assert attn(ws=C.c_void_p(256), wsb=need - 1) == -6 and attn(ws=C.c_void_p(264), wsb=need) == -6
+    assert rf.rf_attention_workspace_bytes(1, 2, 80, L) == 0
 
     def arm(Q=one, K=one, B=1, nH=2, D=64, lay=L, mode=0, thr=0.9, hc=one, ws=one, wsb=1 << 20):
         return lib.rf_arm_classify(Q, K, B, nH, D, C.byref(lay) if lay else None, None, mode, thr, hc, None, ws, wsb,
