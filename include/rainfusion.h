@@ -47,6 +47,8 @@ typedef struct {
     int32_t sample_interval;
 } rf_params;
 
+#define RF_MAX_BANDWIDTHS 4 /* candidate bandwidths of the per-head bandwidth variant */
+
 enum rf_head_class { RF_SPATIAL = 0, RF_TEMPORAL = 1, RF_TEXTURAL = 2, RF_DENSE = 3 };
 enum rf_sample_mode { RF_SAMPLE_FIRST_FRAME = 0, RF_SAMPLE_EQUAL_INTERVAL = 1 };
 enum rf_status {
@@ -85,6 +87,24 @@ int rf_arm_classify(const void *Q, const void *K, int B, int nH, int D, const rf
 size_t rf_arm_workspace_bytes(int B, int nH, const rf_layout *layout, const rf_params *params);
 
 /*
+ * RainFusion+ (Sec. 4.3): ARM with per-head bandwidth.  Alg. 1's two recalls are measured once
+ * per candidate bandwidth (bandwidths[k] replaces both bw_temporal and bw_spatial of `params`),
+ * in the same pass over the sampled scores.  A head is TEMPORAL with the narrowest candidate
+ * whose R_hat >= threshold if there is one, else SPATIAL with the narrowest candidate whose
+ * R_tilde >= threshold, else TEXTURAL (the paper uses candidates 0.5, 0.25, 0.125 and 90 %).
+ * bandwidths  : HOST, float [n_bw], each in [0, 1], 1 <= n_bw <= RF_MAX_BANDWIDTHS, any order.
+ * head_class  : device, int32 [B*nH], written.
+ * head_bw     : device, int32 [B*nH], written: index into bandwidths, -1 for TEXTURAL heads.
+ * recalls     : device, float [B*nH][2][n_bw] = R_hat per candidate, then R_tilde per candidate; may be NULL.
+ * workspace   : device scratch of at least n_bw * rf_arm_workspace_bytes() bytes.
+ * Everything else as rf_arm_classify.
+ */
+int rf_arm_classify_plus(const void *Q, const void *K, int B, int nH, int D, const rf_layout *layout,
+                         const rf_params *params, int sample_mode, float threshold, const float *bandwidths,
+                         int n_bw, int32_t *head_class, int32_t *head_bw, float *recalls, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
+/*
  * Sparse attention forward, Eq. 1-2 with the mask of each head's pattern (Eq. 3-5):
  *   O[b,h,i,:] = sum_j softmax_j(q_i . k_j / sqrt(D) over kept j) * v_j.
  * The mask is token-level; `block` (64 or 128) is the number of query rows per block, and
@@ -104,6 +124,18 @@ size_t rf_arm_workspace_bytes(int B, int nH, const rf_layout *layout, const rf_p
 int rf_sparse_attention(const void *Q, const void *K, const void *V, const int32_t *head_class, int B,
                         int nH, int D, const rf_layout *layout, const rf_params *params, int block,
                         void *O, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Sparse attention with per-head bandwidth (the attention half of RainFusion+): as
+ * rf_sparse_attention, but head (b, h) uses bandwidths[head_bw[b*nH + h]] for its Spatial or
+ * Temporal band instead of params' (TEXTURAL and DENSE heads, and indices outside 0..n_bw-1,
+ * ignore it / fall back to bandwidths[0]).
+ * head_bw     : device, int32 [B*nH].   bandwidths : HOST, float [n_bw], 1 <= n_bw <= RF_MAX_BANDWIDTHS.
+ */
+int rf_sparse_attention_plus(const void *Q, const void *K, const void *V, const int32_t *head_class,
+                             const int32_t *head_bw, const float *bandwidths, int n_bw, int B, int nH, int D,
+                             const rf_layout *layout, const rf_params *params, int block, void *O,
+                             void *workspace, size_t workspace_bytes, void *stream);
 
 /* Bytes of the optional workspace of rf_sparse_attention (room for K_C and V_C of every head);
  * 0 if the arguments are invalid. */

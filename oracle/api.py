@@ -94,6 +94,9 @@ def _L():
         lib.rfo_arm_recall.argtypes = [f32p, f32p, C.c_int, PL, PP, C.c_int, C.c_int, f64p]
         lib.rfo_arm_classify.restype = C.c_int
         lib.rfo_arm_classify.argtypes = [f32p, f32p, C.c_int, PL, PP, C.c_int, C.c_double, f64p]
+        lib.rfo_arm_classify_plus.restype = C.c_int
+        lib.rfo_arm_classify_plus.argtypes = [f32p, f32p, C.c_int, PL, PP, C.c_int, C.c_double, f64p, C.c_int,
+                                              C.POINTER(C.c_int), f64p]
         lib.rfo_decide.restype = C.c_int
         lib.rfo_decide.argtypes = [C.c_double, C.c_double, C.c_double]
         lib.rfo_keep_matrix.restype = None
@@ -201,6 +204,19 @@ def arm_classify(Q, K, L, P=Params(), sample_mode=SAMPLE_FIRST_FRAME, alpha=0.9)
     c = _L().rfo_arm_classify(_p(Q, C.c_float), _p(K, C.c_float), D, C.byref(L.c()),
                               C.byref(P.c()), sample_mode, float(alpha), rec)
     return int(c), (rec[0], rec[1])
+
+
+def arm_classify_plus(Q, K, L, P, sample_mode, alpha, bandwidths):
+    """RainFusion+ on one head. Returns (class, bandwidth index or -1, recalls [2, n_bw])."""
+    N, D = num_tokens(L), Q.shape[-1]
+    Q, K = _f32(Q, N, D), _f32(K, N, D)
+    bws = np.array([float(np.float32(b)) for b in bandwidths], dtype=np.float64)
+    rec = np.empty((2, len(bws)), dtype=np.float64)
+    idx = C.c_int(-2)
+    c = _L().rfo_arm_classify_plus(_p(Q, C.c_float), _p(K, C.c_float), D, C.byref(L.c()), C.byref(P.c()),
+                                   sample_mode, float(alpha), _p(bws, C.c_double), len(bws), C.byref(idx),
+                                   _p(rec, C.c_double))
+    return int(c), idx.value, rec
 
 
 def decide(r_hat, r_tilde, alpha):

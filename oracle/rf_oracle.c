@@ -267,6 +267,38 @@ int rfo_arm_classify(const float *Q, const float *K, int D, const rfo_layout *L,
     return RFO_TEXTURAL;
 }
 
+/*
+ * RainFusion+ (Sec. 4.3, "dynamic bandwidth selection (0.5, 0.25, 0.125) across different
+ * attention heads ... the minimum value that maintains 90% recall"), one head.  The recalls of
+ * Alg. 1 are evaluated once per candidate bandwidth bws[k] (the Temporal recall with
+ * bw_temporal = bws[k], the Spatial recall with bw_spatial = bws[k]).  Reading taken: Alg. 1's
+ * order is kept -- if any candidate gives R-hat >= alpha the head is Temporal with the smallest
+ * such bandwidth; else if any gives R-tilde >= alpha it is Spatial with the smallest such
+ * bandwidth; else Textural (*bw_index = -1).
+ * recalls (optional): [2][n_bw], row 0 = R-hat per candidate, row 1 = R-tilde per candidate.
+ */
+int rfo_arm_classify_plus(const float *Q, const float *K, int D, const rfo_layout *L, const rfo_params *P,
+                          int sample_mode, double alpha, const double *bws, int n_bw, int *bw_index,
+                          double *recalls)
+{
+    int best_t = -1, best_s = -1;
+    for (int k = 0; k < n_bw; ++k) {
+        rfo_params pk = *P;
+        pk.bw_temporal = bws[k];
+        pk.bw_spatial = bws[k];
+        const double r_hat =
+            rfo_arm_recall(Q, K, D, L, &pk, sample_mode == RFO_SAMPLE_EQUAL_INTERVAL, RFO_TEMPORAL, NULL);
+        const double r_tilde = rfo_arm_recall(Q, K, D, L, &pk, 1, RFO_SPATIAL, NULL);
+        if (recalls) { recalls[k] = r_hat; recalls[n_bw + k] = r_tilde; }
+        if (r_hat >= alpha && (best_t < 0 || bws[k] < bws[best_t])) best_t = k;
+        if (r_tilde >= alpha && (best_s < 0 || bws[k] < bws[best_s])) best_s = k;
+    }
+    if (best_t >= 0) { *bw_index = best_t; return RFO_TEMPORAL; }
+    if (best_s >= 0) { *bw_index = best_s; return RFO_SPATIAL; }
+    *bw_index = -1;
+    return RFO_TEXTURAL;
+}
+
 /* The decision rule alone, for truth-table tests. */
 int rfo_decide(double r_hat, double r_tilde, double alpha)
 {

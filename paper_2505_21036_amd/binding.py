@@ -67,6 +67,13 @@ def load_library():
                                         vp]
     lib.rf_attention_workspace_bytes.restype = C.c_size_t
     lib.rf_attention_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, PL, PP]
+    fp = C.POINTER(C.c_float)
+    lib.rf_arm_classify_plus.restype = C.c_int
+    lib.rf_arm_classify_plus.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, PL, PP, C.c_int, C.c_float, fp, C.c_int, vp,
+                                         vp, vp, vp, C.c_size_t, vp]
+    lib.rf_sparse_attention_plus.restype = C.c_int
+    lib.rf_sparse_attention_plus.argtypes = [vp, vp, vp, vp, vp, fp, C.c_int, C.c_int, C.c_int, C.c_int, PL, PP, C.c_int,
+                                             vp, vp, C.c_size_t, vp]
     lib.rf_plan_host.restype = C.c_int
     lib.rf_plan_host.argtypes = [PL, PP, C.c_int, C.c_int, vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
     lib.rf_plan_order.restype = C.c_int
@@ -129,6 +136,57 @@ def rf_arm_classify(Q, K, layout, params=None, sample_mode=RF_SAMPLE_FIRST_FRAME
     if st != 0:
         raise RfError(st, "rf_arm_classify")
     return head_class, recalls
+
+
+def rf_arm_classify_plus(Q, K, layout, params, sample_mode, threshold, bandwidths):
+    """RainFusion+ ARM. Returns (head_class [B, nH], head_bw [B, nH], recalls [B, nH, 2, n_bw]) on the device."""
+    import torch
+    _check_bf16(Q, "Q")
+    _check_bf16(K, "K", Q.shape)
+    B, nH, N, D = Q.shape
+    if N != layout.T * layout.H * layout.W + layout.text_len:
+        raise ValueError("N does not match the layout")
+    n_bw = len(bandwidths)
+    bws = (C.c_float * n_bw)(*bandwidths)
+    head_class = torch.empty(B, nH, dtype=torch.int32, device=Q.device)
+    head_bw = torch.empty(B, nH, dtype=torch.int32, device=Q.device)
+    recalls = torch.empty(B, nH, 2, n_bw, dtype=torch.float32, device=Q.device)
+    workspace = torch.empty(max(n_bw * rf_arm_workspace_bytes(B, nH, layout, params), 4), dtype=torch.uint8,
+                            device=Q.device)
+    st = load_library().rf_arm_classify_plus(Q.data_ptr(), K.data_ptr(), B, nH, D, C.byref(layout), _pp(params),
+                                             sample_mode, threshold, bws, n_bw, head_class.data_ptr(),
+                                             head_bw.data_ptr(), recalls.data_ptr(), workspace.data_ptr(),
+                                             workspace.numel(), _stream())
+    if st != 0:
+        raise RfError(st, "rf_arm_classify_plus")
+    return head_class, head_bw, recalls
+
+
+def rf_sparse_attention_plus(Q, K, V, head_class, head_bw, bandwidths, layout, params=None, block=128, out=None,
+                             workspace=None):
+    """Sparse attention with per-head bandwidth (RainFusion+). head_bw: int32 device tensor [B, nH]."""
+    import torch
+    _check_bf16(Q, "Q")
+    _check_bf16(K, "K", Q.shape)
+    _check_bf16(V, "V", Q.shape)
+    B, nH, N, D = Q.shape
+    if N != layout.T * layout.H * layout.W + layout.text_len:
+        raise ValueError("N does not match the layout")
+    for t, name in ((head_class, "head_class"), (head_bw, "head_bw")):
+        if not (t.is_cuda and t.dtype == torch.int32 and t.is_contiguous() and t.numel() == B * nH):
+            raise ValueError("%s must be a contiguous int32 device tensor with B*nH entries" % name)
+    if out is None:
+        out = torch.empty_like(Q)
+    n_bw = len(bandwidths)
+    bws = (C.c_float * n_bw)(*bandwidths)
+    ws_ptr, ws_bytes = (None, 0) if workspace is None else (workspace.data_ptr(),
+                                                           workspace.numel() * workspace.element_size())
+    st = load_library().rf_sparse_attention_plus(Q.data_ptr(), K.data_ptr(), V.data_ptr(), head_class.data_ptr(),
+                                                 head_bw.data_ptr(), bws, n_bw, B, nH, D, C.byref(layout), _pp(params),
+                                                 block, out.data_ptr(), ws_ptr, ws_bytes, _stream())
+    if st != 0:
+        raise RfError(st, "rf_sparse_attention_plus")
+    return out
 
 
 def rf_attention_workspace_bytes(B, nH, D, layout, params=None):

@@ -3,6 +3,7 @@
 // be exercised on a machine without a GPU.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <memory>
@@ -179,9 +180,27 @@ size_t rf_arm_workspace_bytes(int B, int nH, const rf_layout* layout, const rf_p
     return static_cast<size_t>(B) * nH * 2 * arm_rows(g) * sizeof(float);
 }
 
-int rf_arm_classify(const void* Q, const void* K, int B, int nH, int D, const rf_layout* layout,
-                    const rf_params* params, int sample_mode, float threshold, int32_t* head_class,
-                    float* recalls, void* workspace, size_t workspace_bytes, void* stream) {
+// Geometry of `params` with both band widths replaced by bw.
+static int geometry_with_bandwidth(const rf_layout* layout, const rf_params* params, float bw, Geometry* g) {
+    rf_params p = params ? *params : rf_params{0.25f, 0.25f, 2, 0};
+    p.bw_spatial = bw;
+    p.bw_temporal = bw;
+    return resolve_geometry(layout, &p, g);
+}
+
+static int check_bandwidths(const float* bandwidths, int n_bw) {
+    if (!bandwidths) return RF_ERR_NULL;
+    if (n_bw < 1 || n_bw > RF_MAX_BANDWIDTHS) return RF_ERR_PARAM;
+    for (int k = 0; k < n_bw; ++k)
+        if (!(bandwidths[k] >= 0.f && bandwidths[k] <= 1.f)) return RF_ERR_PARAM;
+    return RF_OK;
+}
+
+// Shared by rf_arm_classify (bandwidths == null: the widths of params) and rf_arm_classify_plus.
+static int arm_classify_impl(const void* Q, const void* K, int B, int nH, int D, const rf_layout* layout,
+                             const rf_params* params, int sample_mode, float threshold, const float* bandwidths,
+                             int n_bw, int32_t* head_class, int32_t* head_bw, float* recalls, void* workspace,
+                             size_t workspace_bytes, void* stream) {
     if (!Q || !K || !head_class || !layout) return RF_ERR_NULL;
     Geometry g;
     int st = resolve_geometry(layout, params, &g);
@@ -190,27 +209,68 @@ int rf_arm_classify(const void* Q, const void* K, int B, int nH, int D, const rf
     if (st != RF_OK) return st;
     if (sample_mode != RF_SAMPLE_FIRST_FRAME && sample_mode != RF_SAMPLE_EQUAL_INTERVAL) return RF_ERR_PARAM;
     if (!(threshold >= 0.f && threshold <= 1.f)) return RF_ERR_PARAM;
-    if (!workspace || workspace_bytes < rf_arm_workspace_bytes(B, nH, layout, params)) return RF_ERR_WORKSPACE;
+    if (bandwidths) {
+        st = check_bandwidths(bandwidths, n_bw);
+        if (st != RF_OK) return st;
+    }
+    if (!workspace || workspace_bytes < n_bw * rf_arm_workspace_bytes(B, nH, layout, params)) return RF_ERR_WORKSPACE;
+
+    int r_temporal[kMaxBw] = {g.r_temporal}, r_spatial[kMaxBw] = {g.r_spatial};
+    ArmArgs a{};
+    a.n_bw = n_bw;
+    for (int k = 0; k < n_bw; ++k) a.by_width[k] = k;
+    if (bandwidths) {
+        for (int k = 0; k < n_bw; ++k) {
+            Geometry gk;
+            st = geometry_with_bandwidth(layout, params, bandwidths[k], &gk);
+            if (st != RF_OK) return st;
+            r_temporal[k] = gk.r_temporal;
+            r_spatial[k] = gk.r_spatial;
+        }
+        std::stable_sort(a.by_width, a.by_width + n_bw, [&](int x, int y) { return bandwidths[x] < bandwidths[y]; });
+    }
 
     const CachedPlan* tb = nullptr;
     st = get_arm_tables(g, &tb);
     if (st != RF_OK) return st;
 
-    ArmArgs a{};
     a.Q = static_cast<const uint16_t*>(Q);
     a.K = static_cast<const uint16_t*>(K);
     a.BH = B * nH;
     a.N = g.N;
     a.scale_log2 = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(D)));
-    if (sample_mode == RF_SAMPLE_FIRST_FRAME) a.pass[0] = ArmPass{tb->local_pos, g.HW, 1, g.r_temporal};
-    else a.pass[0] = ArmPass{tb->global_pos, tb->nG, g.omega, g.r_temporal};
-    a.pass[1] = ArmPass{tb->global_frame, tb->nG, g.omega, g.r_spatial};
+    if (sample_mode == RF_SAMPLE_FIRST_FRAME) a.pass[0] = ArmPass{tb->local_pos, g.HW, 1, {0}};
+    else a.pass[0] = ArmPass{tb->global_pos, tb->nG, g.omega, {0}};
+    a.pass[1] = ArmPass{tb->global_frame, tb->nG, g.omega, {0}};
+    for (int k = 0; k < n_bw; ++k) {
+        a.pass[0].radius[k] = r_temporal[k];
+        a.pass[1].radius[k] = r_spatial[k];
+    }
     a.row_recall = static_cast<float*>(workspace);
     a.max_n = static_cast<int>(arm_rows(g));
     a.threshold = threshold;
     a.head_class = head_class;
+    a.head_bw = head_bw;
     a.recalls = recalls;
     return launch_arm(a, D, stream) == 0 ? RF_OK : RF_ERR_HIP;
+}
+
+int rf_arm_classify(const void* Q, const void* K, int B, int nH, int D, const rf_layout* layout,
+                    const rf_params* params, int sample_mode, float threshold, int32_t* head_class,
+                    float* recalls, void* workspace, size_t workspace_bytes, void* stream) {
+    return arm_classify_impl(Q, K, B, nH, D, layout, params, sample_mode, threshold, nullptr, 1, head_class, nullptr,
+                             recalls, workspace, workspace_bytes, stream);
+}
+
+int rf_arm_classify_plus(const void* Q, const void* K, int B, int nH, int D, const rf_layout* layout,
+                         const rf_params* params, int sample_mode, float threshold, const float* bandwidths,
+                         int n_bw, int32_t* head_class, int32_t* head_bw, float* recalls, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+    if (!head_bw) return RF_ERR_NULL;
+    const int st = check_bandwidths(bandwidths, n_bw);
+    if (st != RF_OK) return st;
+    return arm_classify_impl(Q, K, B, nH, D, layout, params, sample_mode, threshold, bandwidths, n_bw, head_class,
+                             head_bw, recalls, workspace, workspace_bytes, stream);
 }
 
 static size_t packed_count(const Geometry& g) {
@@ -226,9 +286,10 @@ size_t rf_attention_workspace_bytes(int B, int nH, int D, const rf_layout* layou
     return 2 * static_cast<size_t>(B) * nH * packed_count(g) * D * sizeof(uint16_t);
 }
 
-int rf_sparse_attention(const void* Q, const void* K, const void* V, const int32_t* head_class, int B, int nH,
-                        int D, const rf_layout* layout, const rf_params* params, int block, void* O,
-                        void* workspace, size_t workspace_bytes, void* stream) {
+static int sparse_attention_impl(const void* Q, const void* K, const void* V, const int32_t* head_class,
+                                 const int32_t* head_bw, const float* bandwidths, int n_bw, int B, int nH, int D,
+                                 const rf_layout* layout, const rf_params* params, int block, void* O, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
     if (!Q || !K || !V || !O || !head_class || !layout) return RF_ERR_NULL;
     Geometry g;
     int st = resolve_geometry(layout, params, &g);
@@ -239,25 +300,51 @@ int rf_sparse_attention(const void* Q, const void* K, const void* V, const int32
     if (workspace && workspace_bytes < rf_attention_workspace_bytes(B, nH, D, layout, params)) return RF_ERR_WORKSPACE;
     if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 15)) return RF_ERR_WORKSPACE;
 
-    const DevicePlan* dp = nullptr;
-    st = get_attention_plan(g, block, &dp);
-    if (st != RF_OK) return st;
-
     AttnArgs a{};
+    a.n_plans = bandwidths ? n_bw : 1;
+    for (int k = 0; k < a.n_plans; ++k) {
+        Geometry gk = g;
+        if (bandwidths) {
+            st = geometry_with_bandwidth(layout, params, bandwidths[k], &gk);
+            if (st != RF_OK) return st;
+        }
+        const DevicePlan* dp = nullptr;
+        st = get_attention_plan(gk, block, &dp);
+        if (st != RF_OK) return st;
+        a.plan[k] = *dp;
+    }
     a.Q = static_cast<const uint16_t*>(Q);
     a.K = static_cast<const uint16_t*>(K);
     a.V = static_cast<const uint16_t*>(V);
     a.O = static_cast<uint16_t*>(O);
     a.head_class = head_class;
+    a.head_bw = bandwidths ? head_bw : nullptr;
     a.BH = B * nH;
     a.scale_log2 = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(D)));
-    a.plan = *dp;
     if (workspace) {
         a.packed_k = static_cast<uint16_t*>(workspace);
-        a.packed_v = a.packed_k + static_cast<size_t>(B) * nH * dp->Nc * D;
+        a.packed_v = a.packed_k + static_cast<size_t>(B) * nH * a.plan[0].Nc * D;
         if (launch_pack_textural(a, D, stream) != 0) return RF_ERR_HIP;
     }
     return launch_attention(a, D, stream) == 0 ? RF_OK : RF_ERR_HIP;
+}
+
+int rf_sparse_attention(const void* Q, const void* K, const void* V, const int32_t* head_class, int B, int nH,
+                        int D, const rf_layout* layout, const rf_params* params, int block, void* O,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+    return sparse_attention_impl(Q, K, V, head_class, nullptr, nullptr, 1, B, nH, D, layout, params, block, O,
+                                 workspace, workspace_bytes, stream);
+}
+
+int rf_sparse_attention_plus(const void* Q, const void* K, const void* V, const int32_t* head_class,
+                             const int32_t* head_bw, const float* bandwidths, int n_bw, int B, int nH, int D,
+                             const rf_layout* layout, const rf_params* params, int block, void* O, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+    if (!head_bw) return RF_ERR_NULL;
+    const int st = check_bandwidths(bandwidths, n_bw);
+    if (st != RF_OK) return st;
+    return sparse_attention_impl(Q, K, V, head_class, head_bw, bandwidths, n_bw, B, nH, D, layout, params, block, O,
+                                 workspace, workspace_bytes, stream);
 }
 
 int rf_plan_host(const rf_layout* layout, const rf_params* params, int block, int cls, int32_t* row_ptr,

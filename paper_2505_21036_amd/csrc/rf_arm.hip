@@ -39,7 +39,10 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
     load_q_frags<D>(Qh, qsc * ps.stride, hf, qf);
     const int q_attr = ps.attr[qsc];
 
-    float m_run = -INFINITY, l_all = 0.f, l_kept = 0.f;
+    float m_run = -INFINITY, l_all = 0.f, l_kept[kMaxBw];
+#pragma unroll
+    for (int b = 0; b < kMaxBw; ++b) l_kept[b] = 0.f;
+    const int n_bw = a.n_bw;
     const float c = a.scale_log2;
     const int ntiles = (n + kTileK - 1) / kTileK;
 
@@ -82,57 +85,77 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
         const float m_new = fmaxf(m_run, mt);  // finite: every tile holds at least one real sample
         const float alpha = fast_exp2((m_run - m_new) * c);
         const float mc = m_new * c;
-        float sum_all = 0.f, sum_kept = 0.f;
+        float sum_all = 0.f, sum_kept[kMaxBw];
+#pragma unroll
+        for (int b = 0; b < kMaxBw; ++b) sum_kept[b] = 0.f;
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const float p = fast_exp2(fmaf(s[kb2][r], c, -mc));
                 const int d = q_attr - al[32 * kb2 + key_of_reg(r, hf)];
+                const int dist = d < 0 ? -d : d;
                 sum_all += p;
-                sum_kept += ((d < 0 ? -d : d) <= ps.radius) ? p : 0.f;
+                sum_kept[0] += dist <= ps.radius[0] ? p : 0.f;
+                if (n_bw > 1) {  // uniform: the per-head bandwidth variant measures every candidate at once
+#pragma unroll
+                    for (int b = 1; b < kMaxBw; ++b) sum_kept[b] += (b < n_bw && dist <= ps.radius[b]) ? p : 0.f;
+                }
             }
         l_all = l_all * alpha + sum_all;
-        l_kept = l_kept * alpha + sum_kept;
+#pragma unroll
+        for (int b = 0; b < kMaxBw; ++b) l_kept[b] = l_kept[b] * alpha + sum_kept[b];
         m_run = m_new;
 
         if (t + 1 < ntiles) stash_tile(t + 1);
         __syncthreads();
     }
     l_all += other_half(l_all);
-    l_kept += other_half(l_kept);
-    if (hf == 0 && qs < n)
-        a.row_recall[(static_cast<size_t>(bh) * 2 + pass) * a.max_n + qs] = l_kept / l_all;  // Eq. 6, one row
+#pragma unroll
+    for (int b = 0; b < kMaxBw; ++b) {
+        if (b >= n_bw) break;
+        const float kept = l_kept[b] + other_half(l_kept[b]);
+        if (hf == 0 && qs < n)
+            a.row_recall[((static_cast<size_t>(bh) * 2 + pass) * n_bw + b) * a.max_n + qs] = kept / l_all;  // Eq. 6, one row
+    }
 }
 
-// Mean of the per-row recalls in a fixed summation order, then Alg. 1's rule.
+// Mean of the per-row recalls in a fixed summation order, then Alg. 1's rule (with several
+// candidate bandwidths: the narrowest one that holds the threshold, Temporal before Spatial).
 __global__ void __launch_bounds__(256) arm_finish_kernel(ArmArgs a) {
     __shared__ float red[256];
-    const int bh = blockIdx.x, tid = threadIdx.x;
-    float rec[2];
-    for (int pass = 0; pass < 2; ++pass) {
-        const int n = a.pass[pass].n;
-        const float* rr = a.row_recall + (static_cast<size_t>(bh) * 2 + pass) * a.max_n;
-        float acc = 0.f;
-        for (int i = tid; i < n; i += 256) acc += rr[i];
-        red[tid] = acc;
-        __syncthreads();
-        for (int w = 128; w > 0; w >>= 1) {
-            if (tid < w) red[tid] += red[tid + w];
+    __shared__ float rec[2][kMaxBw];
+    const int bh = blockIdx.x, tid = threadIdx.x, n_bw = a.n_bw;
+    for (int pass = 0; pass < 2; ++pass)
+        for (int b = 0; b < n_bw; ++b) {
+            const int n = a.pass[pass].n;
+            const float* rr = a.row_recall + ((static_cast<size_t>(bh) * 2 + pass) * n_bw + b) * a.max_n;
+            float acc = 0.f;
+            for (int i = tid; i < n; i += 256) acc += rr[i];
+            red[tid] = acc;
+            __syncthreads();
+            for (int w = 128; w > 0; w >>= 1) {
+                if (tid < w) red[tid] += red[tid + w];
+                __syncthreads();
+            }
+            if (tid == 0) rec[pass][b] = red[0] / static_cast<float>(n);
             __syncthreads();
         }
-        rec[pass] = red[0] / static_cast<float>(n);
-        __syncthreads();
-    }
     if (tid == 0) {
-        int cls = RF_TEXTURAL;
-        if (rec[0] >= a.threshold) cls = RF_TEMPORAL;  // Temporal has priority
-        else if (rec[1] >= a.threshold) cls = RF_SPATIAL;
+        int cls = RF_TEXTURAL, chosen = -1;
+        for (int pass = 0; pass < 2 && chosen < 0; ++pass)  // Temporal (pass 0) has priority
+            for (int i = 0; i < n_bw && chosen < 0; ++i) {
+                const int b = a.by_width[i];
+                if (rec[pass][b] >= a.threshold) {
+                    chosen = b;
+                    cls = pass == 0 ? RF_TEMPORAL : RF_SPATIAL;
+                }
+            }
         a.head_class[bh] = cls;
-        if (a.recalls) {
-            a.recalls[2 * bh] = rec[0];
-            a.recalls[2 * bh + 1] = rec[1];
-        }
+        if (a.head_bw) a.head_bw[bh] = chosen;
+        if (a.recalls)
+            for (int pass = 0; pass < 2; ++pass)
+                for (int b = 0; b < n_bw; ++b) a.recalls[(bh * 2 + pass) * n_bw + b] = rec[pass][b];
     }
 }
 

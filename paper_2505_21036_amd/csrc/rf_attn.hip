@@ -187,11 +187,10 @@ struct QueryBlock {
 constexpr float kRescaleSlack = 8.f;
 
 template <int D, int NW, int MODE>
-__device__ __forceinline__ void attend(const AttnArgs& a, const QueryBlock& qk, unsigned char* smem) {
+__device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, const QueryBlock& qk, unsigned char* smem) {
     constexpr int BQ = 32 * NW;
     using ST = typename TileFor<D, NW>::type;
     using SM = AttnSmem<D, NW>;
-    const DevicePlan& pl = a.plan;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, m = lane & 31;
     const int N = pl.N, Nv = pl.Nv, keyN = qk.keyN, ntiles = qk.ntiles;
     // per-key side data staged through LDS two tiles ahead: the token index of each key of the
@@ -460,18 +459,24 @@ constexpr int attn_waves_per_simd(int D, int NW) { return (D == 64 && NW == 4) ?
 template <int D, int NW>
 __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(attn_waves_per_simd(D, NW), attn_waves_per_simd(D, NW)))) attn_kernel(AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const DevicePlan& pl = a.plan;
     // Workgroup ids go to the 8 XCDs round-robin.  Every XCD takes one eighth of a head's query
     // blocks, a contiguous run of the pattern's block order (neighbours in that order walk nearly
     // the same key tiles, which they then share through the XCD's L2), and all XCDs move through
     // the heads together, so the K/V of the head in flight (tens of MB) stays resident in the
     // memory-side cache for whatever misses L2.
-    const int per_xcd = (pl.nQB + 7) >> 3;
+    const int nQB = a.plan[0].nQB, per_xcd = (nQB + 7) >> 3;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int ordinal = xcd * per_xcd + slot % per_xcd;
-    if (ordinal >= pl.nQB) return;
+    if (ordinal >= nQB) return;
     QueryBlock qk;
     qk.bh = slot / per_xcd;
+    // per-head bandwidth: the plans differ only in the Spatial / Temporal lists, radii and block order
+    int which = 0;
+    if (a.head_bw) {
+        which = a.head_bw[qk.bh];
+        if (static_cast<unsigned>(which) >= static_cast<unsigned>(a.n_plans)) which = 0;
+    }
+    const DevicePlan& pl = a.plan[which];
     int cls = a.head_class[qk.bh];
     if (static_cast<unsigned>(cls) > 3u) cls = RF_DENSE;
     qk.cls = cls;
@@ -483,7 +488,7 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
     if (cls == RF_DENSE) {
         qk.ntiles = pl.nKT;
         qk.keyN = pl.N;
-        attend<D, NW, MODE_ALL>(a, qk, smem);
+        attend<D, NW, MODE_ALL>(a, pl, qk, smem);
     } else if (cls == RF_TEXTURAL && qk.qb < pl.first_text_qb) {
         // Textural query blocks made only of video tokens see the compacted key sequence (Eq. 5):
         // as a packed copy made by pack_textural_kernel if the caller gave room for one, else
@@ -494,16 +499,16 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
             const size_t packed_bytes = static_cast<size_t>(qk.bh) * pl.Nc * D * 2;
             qk.kbase = reinterpret_cast<const unsigned char*>(a.packed_k) + packed_bytes;
             qk.vbase = reinterpret_cast<const unsigned char*>(a.packed_v) + packed_bytes;
-            attend<D, NW, MODE_ALL>(a, qk, smem);
+            attend<D, NW, MODE_ALL>(a, pl, qk, smem);
         } else {
-            attend<D, NW, MODE_COMPACT>(a, qk, smem);
+            attend<D, NW, MODE_COMPACT>(a, pl, qk, smem);
         }
     } else {
         const int e0 = pl.row_ptr[cls][qk.qb];
         qk.ntiles = pl.row_ptr[cls][qk.qb + 1] - e0;
         qk.cols = pl.cols[cls] + e0;
         qk.keyN = pl.N;
-        attend<D, NW, MODE_LISTED>(a, qk, smem);
+        attend<D, NW, MODE_LISTED>(a, pl, qk, smem);
     }
 }
 
@@ -511,7 +516,7 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
 // rows) copied in order into the caller's workspace.  One workgroup per (64 packed rows, head).
 template <int D>
 __global__ void __launch_bounds__(256) pack_textural_kernel(AttnArgs a) {
-    const DevicePlan& pl = a.plan;
+    const DevicePlan& pl = a.plan[0];
     const int bh = blockIdx.y;
     if (a.head_class[bh] != RF_TEXTURAL) return;
     constexpr int CH = D / 8;  // 16-byte chunks per row
@@ -528,7 +533,7 @@ __global__ void __launch_bounds__(256) pack_textural_kernel(AttnArgs a) {
 
 int launch_pack_textural(const AttnArgs& a, int D, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const dim3 grid(a.plan.nCT, a.BH);
+    const dim3 grid(a.plan[0].nCT, a.BH);
     if (D == 64) hipLaunchKernelGGL(pack_textural_kernel<64>, grid, dim3(256), 0, st, a);
     else if (D == 96) hipLaunchKernelGGL(pack_textural_kernel<96>, grid, dim3(256), 0, st, a);
     else if (D == 128) hipLaunchKernelGGL(pack_textural_kernel<128>, grid, dim3(256), 0, st, a);
@@ -547,14 +552,14 @@ static int launch_one(const AttnArgs& a, hipStream_t st) {
         if (e != hipSuccess) return static_cast<int>(e);
         configured = true;
     }
-    const int grid = 8 * ((a.plan.nQB + 7) / 8) * a.BH;
+    const int grid = 8 * ((a.plan[0].nQB + 7) / 8) * a.BH;
     hipLaunchKernelGGL((attn_kernel<D, NW>), dim3(grid), dim3(NT), smem, st, a);
     return static_cast<int>(hipGetLastError());
 }
 
 int launch_attention(const AttnArgs& a, int D, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int nw = a.plan.block / 32;
+    const int nw = a.plan[0].block / 32;
     if (D == 64 && nw == 2) return launch_one<64, 2>(a, st);
     if (D == 64 && nw == 4) return launch_one<64, 4>(a, st);
     if (D == 96 && nw == 2) return launch_one<96, 2>(a, st);

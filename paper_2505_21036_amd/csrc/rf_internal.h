@@ -10,6 +10,7 @@
 namespace rf {
 
 constexpr int kTileK = 64;  // keys per LDS tile of the attention and ARM kernels
+constexpr int kMaxBw = RF_MAX_BANDWIDTHS;  // candidate bandwidths of the per-head bandwidth variant
 
 // Flags on a key-tile entry of a block list (RF_PLAN_PARTIAL is public).
 constexpr int32_t kTileBoundary = 0x20000000;  // tile holds text keys or runs past the last key
@@ -62,6 +63,7 @@ struct DevicePlan {
     int block, nQB, nKT, nCT, first_text_qb;
 };
 
+// All plans of one call share the layout and the checkerboard; they differ in the band widths.
 struct AttnArgs {
     const uint16_t* Q;
     const uint16_t* K;
@@ -73,7 +75,9 @@ struct AttnArgs {
     // optional: compacted K and V of Textural heads, [BH][Nc][D] each (null: gather through the index table)
     uint16_t* packed_k;
     uint16_t* packed_v;
-    DevicePlan plan;
+    const int32_t* head_bw;  // optional per-head index into plan[]; null or out of range: plan[0]
+    int n_plans;
+    DevicePlan plan[kMaxBw];
 };
 
 // One ARM pass = one (sampling, mask) pair: sample a -> token a * stride, mask keeps
@@ -82,7 +86,7 @@ struct ArmPass {
     const int32_t* attr;  // device [n]
     int n;                // number of samples
     int stride;           // token stride between samples
-    int radius;
+    int radius[kMaxBw];   // one band half-width per candidate bandwidth
 };
 
 struct ArmArgs {
@@ -91,11 +95,14 @@ struct ArmArgs {
     int BH, N;
     float scale_log2;
     ArmPass pass[2];   // 0: Temporal mask (R_hat), 1: Spatial mask (R_tilde)
-    float* row_recall; // device [BH][2][max_n]
+    int n_bw;          // candidate bandwidths (1 for plain Alg. 1)
+    int by_width[kMaxBw];  // candidate indices from the narrowest bandwidth to the widest
+    float* row_recall; // device [BH][2][n_bw][max_n]
     int max_n;
     float threshold;
     int32_t* head_class;  // device [BH]
-    float* recalls;       // device [BH*2] or null
+    int32_t* head_bw;     // device [BH] or null: chosen candidate index, -1 for Textural heads
+    float* recalls;       // device [BH][2][n_bw] or null
 };
 
 // Kernel launchers (defined in the .hip files). Return a hipError_t as int.

@@ -194,6 +194,66 @@ def test_arm_recovers_planted_structure():
             check(O[b, h][torch.as_tensor(rows, device=DEV)], ref, "planted blk%d head(%d,%d) cls%d" % (block, b, h, hc[b, h]))
 
 
+# ----------------------------------------------------------------------------- RainFusion+ (per-head bandwidth)
+BWS = [0.5, 0.25, 0.125]
+
+
+def plus_compare(w, Q, K, V, mode, alpha, bws, block, rows=None, heads=None):
+    """ARM with candidate bandwidths, then attention with the per-head bandwidth it chose."""
+    rl, ol = lay(w)
+    hc, hbw, rec = rf.rf_arm_classify_plus(Q, K, rl, None, mode, alpha, bws)
+    O = rf.rf_sparse_attention_plus(Q, K, V, hc, hbw, bws, rl, None, block)
+    torch.cuda.synchronize()
+    hc, hbw, rec = hc.cpu().numpy(), hbw.cpu().numpy(), rec.cpu().numpy()
+    near = []
+    for b in range(w.B):
+        for h in range(w.nH):
+            if heads is not None and (b, h) not in heads:
+                continue
+            q, k, v = (f32(t) for t in inp.head_qkv(w, b, h))
+            c, idx, orec = orc.arm_classify_plus(q, k, ol, orc.Params(), mode, alpha, bws)
+            assert np.abs(rec[b, h] - orec).max() <= 1e-3, (b, h, rec[b, h], orec)
+            if np.abs(orec - alpha).min() < 1e-3:
+                near.append((b, h))
+            else:
+                assert (hc[b, h], hbw[b, h]) == (c, idx), (b, h, hc[b, h], hbw[b, h], c, idx, orec)
+            # the attention is checked with whatever the GPU chose, so near-threshold heads are covered too
+            bw = bws[hbw[b, h]] if hbw[b, h] >= 0 else 0.25
+            r = np.arange(w.N) if rows is None else rows
+            ref = orc.attention_rows(q, k, v, int(hc[b, h]), ol, orc.Params(bw, bw, 2), r)
+            check(O[b, h][torch.as_tensor(r, device=DEV)], ref,
+                  "%s plus blk%d head(%d,%d) cls%d bw%g" % (w.name, block, b, h, hc[b, h], bw))
+    print("%s plus alpha %g: heads within 1e-3 of the threshold (exempt from class check): %s" % (w.name, alpha, near),
+          flush=True)
+    return hc, hbw, rec
+
+
+@pytest.mark.parametrize("name", ["tiny", "ragged64", "ragged96", "ragged128"])
+def test_plus_small_shapes(name):
+    w = inp.WORKLOADS[name]
+    print("case plus", name, flush=True)
+    Q, K, V = inp.full_qkv(w, DEV)
+    for alpha in (0.3, 0.45, 0.8):  # i.i.d. heads: recalls ~ mask area, so these thresholds exercise every outcome
+        for mode in (rf.RF_SAMPLE_FIRST_FRAME, rf.RF_SAMPLE_EQUAL_INTERVAL):
+            plus_compare(w, Q, K, V, mode, alpha, BWS, 64 if name == "tiny" else 128)
+    plus_compare(w, Q, K, V, rf.RF_SAMPLE_FIRST_FRAME, 0.45, [0.125, 0.5], 64)  # unsorted, two candidates
+
+
+def test_plus_planted_structure_gets_the_narrowest_band():
+    w = inp.WORKLOADS["planted"]
+    print("case plus planted", flush=True)
+    Q, K, V = inp.full_qkv(w, DEV)
+    rows = np.array(inp.sample_rows(w, 24))
+    heads = {(0, 0), (0, 1), (0, 2), (1, 5), (1, 15)}
+    hc, hbw, rec = plus_compare(w, Q, K, V, rf.RF_SAMPLE_FIRST_FRAME, 0.9, BWS, 128, rows, heads)
+    for b in range(w.B):
+        for h in range(w.nH):
+            cls = inp.planted_class(w, b, h)
+            assert hc[b, h] == cls
+            # the planted structure sits well inside even the narrowest band
+            assert hbw[b, h] == (-1 if cls == rf.RF_TEXTURAL else 2), (b, h, rec[b, h])
+
+
 # ----------------------------------------------------------------------------- paper-sized layers
 def sampled_parity(w, O, classes, heads, per_head, params=orc.Params(), tag=""):
     _, ol = lay(w)

@@ -129,7 +129,8 @@ def test_every_declared_symbol_is_exported():
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = re.findall(r"\b(rf_[a-z_]+)\s*\(", hdr)
     assert set(names) >= {"rf_arm_classify", "rf_sparse_attention", "rf_arm_workspace_bytes", "rf_plan_host",
-                          "rf_attention_workspace_bytes", "rf_plan_order",
+                          "rf_attention_workspace_bytes", "rf_plan_order", "rf_arm_classify_plus",
+                          "rf_sparse_attention_plus",
                           "rf_plan_clear", "rf_status_string", "rf_version"}
     for n in set(names):
         assert getattr(lib, n) is not None
@@ -169,6 +170,21 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     assert arm(ws=None) == -6 and arm(wsb=8) == -6
     assert rf.rf_arm_workspace_bytes(1, 2, L) == 1 * 2 * 2 * 64 * 4
     assert rf.rf_arm_workspace_bytes(0, 2, L) == 0
+    # per-head bandwidth variants: candidate list checked on the host before anything else
+    bw3, bad = (C.c_float * 3)(0.5, 0.25, 0.125), (C.c_float * 2)(0.5, 1.5)
+    big = 1 << 20
+
+    def armp(bws=bw3, n=3, hbw=one, hc=one):
+        return lib.rf_arm_classify_plus(one, one, 1, 2, 64, C.byref(L), None, 0, 0.9, bws, n, hc, hbw, None, one, big, None)
+
+    assert armp(bws=None) == -1 and armp(hbw=None) == -1 and armp(hc=None) == -1
+    assert armp(n=0) == -4 and armp(n=5) == -4 and armp(bws=bad, n=2) == -4
+
+    def attnp(bws=bw3, n=3, hbw=one):
+        return lib.rf_sparse_attention_plus(one, one, one, one, hbw, bws, n, 1, 2, 64, C.byref(L), None, 64, one, None, 0,
+                                            None)
+
+    assert attnp(bws=None) == -1 and attnp(hbw=None) == -1 and attnp(n=9) == -4 and attnp(bws=bad, n=2) == -4
     needed = C.c_size_t(0)
     assert lib.rf_plan_host(C.byref(L), None, 64, 7, None, None, 0, C.byref(needed)) == -4
     assert lib.rf_plan_host(C.byref(L), None, 48, 0, None, None, 0, C.byref(needed)) == -5

@@ -326,3 +326,41 @@ def test_classify_combines_recalls_and_rule():
         assert rh == orc.arm_recall(q, k, L, Params(), mode == orc.SAMPLE_EQUAL_INTERVAL, TEMPORAL)
         assert rt == orc.arm_recall(q, k, L, Params(), True, SPATIAL)
         assert c == orc.decide(rh, rt, 0.5)
+
+
+# ---------------------------------------------------------------- RainFusion+ (Sec. 4.3)
+BWS = (0.5, 0.25, 0.125)
+
+
+def test_plus_with_one_candidate_is_algorithm_one():
+    L = Layout(4, 4, 4)
+    q, k, _ = rand_head(64, 8, 30, 3.0)
+    for alpha in (0.3, 0.6, 0.9):
+        c, idx, rec = orc.arm_classify_plus(q, k, L, Params(), orc.SAMPLE_FIRST_FRAME, alpha, [0.25])
+        c1, (rh, rt) = orc.arm_classify(q, k, L, Params(), orc.SAMPLE_FIRST_FRAME, alpha)
+        assert c == c1 and rec[0, 0] == rh and rec[1, 0] == rt
+        assert idx == (-1 if c == TEXTURAL else 0)
+
+
+def test_plus_recalls_grow_with_bandwidth_and_minimum_is_chosen():
+    L = Layout(8, 4, 8)
+    N = orc.num_tokens(L)
+    _, k, _ = rand_head(N, 8, 31)
+    q = np.zeros_like(k)  # uniform attention: recall = area of the sampled mask, a closed form
+    hat = [band_fraction(32, math.floor(b * 32)) for b in BWS]
+    til = [band_fraction(8, math.floor(b * 8)) for b in BWS]
+    c, idx, rec = orc.arm_classify_plus(q, k, L, Params(), orc.SAMPLE_FIRST_FRAME, 0.7, BWS)
+    np.testing.assert_allclose(rec[0], hat, atol=1e-13)
+    np.testing.assert_allclose(rec[1], til, atol=1e-13)
+    assert rec[0, 0] >= rec[0, 1] >= rec[0, 2] and rec[1, 0] >= rec[1, 1] >= rec[1, 2]
+    # band_fraction(32, 16) = 0.742 is the only Temporal candidate above 0.7
+    assert (c, idx) == (TEMPORAL, 0)
+    c, idx, _ = orc.arm_classify_plus(q, k, L, Params(), orc.SAMPLE_FIRST_FRAME, 0.4, BWS)
+    assert (c, idx) == (TEMPORAL, 1)  # 0.25 -> 0.43 still holds 40 %, 0.125 -> 0.23 does not: minimum that holds
+    c, idx, _ = orc.arm_classify_plus(q, k, L, Params(), orc.SAMPLE_FIRST_FRAME, 0.8, BWS)
+    assert (c, idx) == (SPATIAL, 0)  # Temporal never reaches 0.8; Spatial band_fraction(8, 4) = 0.81 does
+    c, idx, _ = orc.arm_classify_plus(q, k, L, Params(), orc.SAMPLE_FIRST_FRAME, 0.95, BWS)
+    assert (c, idx) == (TEXTURAL, -1)
+    # candidate order must not matter
+    c, idx, _ = orc.arm_classify_plus(q, k, L, Params(), orc.SAMPLE_FIRST_FRAME, 0.4, (0.125, 0.5, 0.25))
+    assert (c, idx) == (TEMPORAL, 2)
