@@ -56,6 +56,12 @@ def main():
     ap.add_argument("--workload", default="hunyuan720p")
     ap.add_argument("--block", type=int, default=0, help="skip-list block (64|128); 0 = the workload's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the step: time the bandwidth / stride settings of the paper's sensitivity "
+                         "table (w = 0.25/0.18/0.13, tau = 2/3/4) against the dense run; prints one JSON line")
+    ap.add_argument("--plus", action="store_true",
+                    help="instead of the step: time RainFusion+ (per-head bandwidth from 0.5/0.25/0.125) on the "
+                         "planted workload, whose heads the ARM can tell apart; prints one JSON line")
     ap.add_argument("--only", default="", help="profiling aid: run just 'step', 'arm', 'thirds', 'dense', every head 'spatial' / 'temporal' / 'textural', or 'copy' (a 1 GiB device copy)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -101,6 +107,55 @@ def main():
             pairs.append((a, b))
         torch.cuda.synchronize()
         return sum(a.elapsed_time(b) for a, b in pairs) / reps
+
+    if args.sweep:
+        attn(dense)
+        ms_dense = event_ms(lambda: attn(dense), 2)
+        rows = []
+        for bw, tau, paper in ((0.25, 2, 1.85), (0.18, 3, 2.50), (0.13, 4, 3.00)):
+            prm = rf.rf_params(bw, bw, tau, 0, 0)
+            ws_s = torch.empty(rf.rf_attention_workspace_bytes(w.B, w.nH, w.D, rl, prm), dtype=torch.uint8, device=dev)
+            row = {"bandwidth": bw, "tex_stride": tau, "paper_speedup_with_10pct_dense_steps": paper}
+            for name, classes in (("spatial", torch.zeros_like(dense)), ("temporal", torch.ones_like(dense)),
+                                  ("textural", torch.full_like(dense, 2)), ("thirds", thirds)):
+                fn = lambda: rf.rf_sparse_attention(Q, K, V, classes, rl, prm, block, O, ws_s)
+                fn()
+                ms = event_ms(fn, 2)
+                kept = sum(kept_pairs(c, w, bw, bw, tau) for c in classes.cpu().flatten().tolist()) / (w.B * w.nH * w.N * w.N)
+                row[name] = {"ms": round(ms, 3), "speedup_vs_dense": round(ms_dense / ms, 3),
+                             "kept_fraction": round(kept, 4), "flop_count_speedup": round(1 / kept, 3),
+                             "speedup_if_10pct_steps_dense": round(1 / (0.1 + 0.9 * ms / ms_dense), 3)}
+            rows.append(row)
+        print(json.dumps({"sweep": rows, "dense_ms": round(ms_dense, 3), "workload": w.name, "block": block}))
+        return
+
+    if args.plus:
+        wp = inp.WORKLOADS["planted"]
+        rlp = rf.rf_layout(wp.T, wp.H, wp.W, wp.text_len)
+        Qp, Kp, Vp = inp.full_qkv(wp, dev)
+        bws = [0.5, 0.25, 0.125]
+        hc_p, hbw_p, _ = rf.rf_arm_classify_plus(Qp, Kp, rlp, None, rf.RF_SAMPLE_FIRST_FRAME, 0.9, bws)
+        hc_b, _ = rf.rf_arm_classify(Qp, Kp, rlp, None, rf.RF_SAMPLE_FIRST_FRAME, 0.9)
+        dense_p = torch.full_like(hc_p, rf.RF_DENSE)
+        Op = torch.empty_like(Qp)
+        runs = {"arm_plus": lambda: rf.rf_arm_classify_plus(Qp, Kp, rlp, None, rf.RF_SAMPLE_FIRST_FRAME, 0.9, bws),
+                "arm_base": lambda: rf.rf_arm_classify(Qp, Kp, rlp, None, rf.RF_SAMPLE_FIRST_FRAME, 0.9),
+                "attention_plus": lambda: rf.rf_sparse_attention_plus(Qp, Kp, Vp, hc_p, hbw_p, bws, rlp, None, wp.block, Op),
+                "attention_base": lambda: rf.rf_sparse_attention(Qp, Kp, Vp, hc_b, rlp, None, wp.block, Op),
+                "attention_dense": lambda: rf.rf_sparse_attention(Qp, Kp, Vp, dense_p, rlp, None, wp.block, Op)}
+        res = {}
+        for name, fn in runs.items():
+            fn()
+            res[name + "_ms"] = round(event_ms(fn, 5), 4)
+        hist = {}
+        for c, b in zip(hc_p.cpu().flatten().tolist(), hbw_p.cpu().flatten().tolist()):
+            key = "%s@%s" % (("spatial", "temporal", "textural", "dense")[c], bws[b] if b >= 0 else "-")
+            hist[key] = hist.get(key, 0) + 1
+        res.update({"workload": wp.name, "block": wp.block, "candidates": bws, "chosen": hist,
+                    "speedup_plus_vs_dense": round(res["attention_dense_ms"] / res["attention_plus_ms"], 3),
+                    "speedup_base_vs_dense": round(res["attention_dense_ms"] / res["attention_base_ms"], 3)})
+        print(json.dumps({"plus": res}))
+        return
 
     if args.only:
         one = {n: torch.full((w.B, w.nH), c, dtype=torch.int32, device=dev)

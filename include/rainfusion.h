@@ -40,12 +40,19 @@ typedef struct {
  *                 in every frame.  Both products are formed in double precision.
  *   tex_stride  : tau of Eq. 4; a key at row y, column x of any frame survives iff (y - x) mod tau == 0.
  *   sample_interval : omega of Sec. 3.3 (global sampling keeps tokens 0, omega, 2*omega, ...); 0 means T.
+ *   flags       : 0, or RF_FLAG_TWO_HEAD.  (The paper's "first 10 % of the timesteps dense" needs no flag:
+ *                 pass RF_DENSE for every head on those steps.)
  * Text tokens attend and are attended densely under every pattern and are never sampled by the ARM. */
 typedef struct {
     float bw_spatial, bw_temporal;
     int32_t tex_stride;
     int32_t sample_interval;
+    int32_t flags; /* RF_FLAG_* */
 } rf_params;
+
+/* Two-head ablation (Sec. 4.2, Tab. 2 rows without "Te"): the ARM sends a head that matches neither
+ * the Temporal nor the Spatial mask to RF_DENSE instead of RF_TEXTURAL. */
+#define RF_FLAG_TWO_HEAD 1
 
 #define RF_MAX_BANDWIDTHS 4 /* candidate bandwidths of the per-head bandwidth variant */
 
@@ -56,7 +63,7 @@ enum rf_status {
     RF_ERR_NULL = -1,      /* a required pointer is NULL */
     RF_ERR_SHAPE = -2,     /* B, nH < 1, D not in {64, 96, 128}, or sizes overflow int32 token indices */
     RF_ERR_LAYOUT = -3,    /* T, H, W < 1 or text_len < 0 */
-    RF_ERR_PARAM = -4,     /* bandwidth outside [0, 1], tex_stride < 1, sample_interval < 0, bad sample_mode,
+    RF_ERR_PARAM = -4,     /* bandwidth outside [0, 1], tex_stride < 1, sample_interval < 0, unknown flags, bad sample_mode,
                               threshold not in [0, 1] or NaN */
     RF_ERR_BLOCK = -5,     /* block not 64 or 128 */
     RF_ERR_WORKSPACE = -6, /* a required workspace is NULL, or a workspace is too small or misaligned */
@@ -71,7 +78,7 @@ enum rf_status {
  *   equal-interval sample.  Recall is the mean over sampled query rows of the softmax
  *   mass (scores Q'K'^T / sqrt(D)) that falls on keys the mask keeps.
  *   head_class = TEMPORAL if R_hat >= threshold, else SPATIAL if R_tilde >= threshold,
- *   else TEXTURAL.
+ *   else TEXTURAL (RF_DENSE under RF_FLAG_TWO_HEAD).
  * Q, K        : device, bf16 [B, nH, N, D].
  * head_class  : device, int32 [B*nH], written.
  * recalls     : device, float [B*nH*2] = {R_hat, R_tilde} per head, written; may be NULL.

@@ -49,6 +49,8 @@ typedef struct {
     double bw_spatial, bw_temporal; /* band half-widths as fractions of T and of H*W */
     int32_t tex_stride;             /* tau of Eq. 4 */
     int32_t sample_interval;        /* omega of Sec. 3.3; <= 0 means T */
+    int32_t two_head;               /* ablation of Sec. 4.2 / Tab. 2: only Spatial and Temporal heads are sparse,
+                                       every other head is computed densely */
 } rfo_params;
 
 static int64_t n_video(const rfo_layout *L) { return (int64_t)L->T * L->H * L->W; }
@@ -264,7 +266,7 @@ int rfo_arm_classify(const float *Q, const float *K, int D, const rfo_layout *L,
     if (recalls) { recalls[0] = r_hat; recalls[1] = r_tilde; }
     if (r_hat >= alpha) return RFO_TEMPORAL; /* Temporal has priority */
     if (r_tilde >= alpha) return RFO_SPATIAL;
-    return RFO_TEXTURAL;
+    return P->two_head ? RFO_DENSE : RFO_TEXTURAL;
 }
 
 /*
@@ -296,7 +298,7 @@ int rfo_arm_classify_plus(const float *Q, const float *K, int D, const rfo_layou
     if (best_t >= 0) { *bw_index = best_t; return RFO_TEMPORAL; }
     if (best_s >= 0) { *bw_index = best_s; return RFO_SPATIAL; }
     *bw_index = -1;
-    return RFO_TEXTURAL;
+    return P->two_head ? RFO_DENSE : RFO_TEXTURAL;
 }
 
 /* The decision rule alone, for truth-table tests. */

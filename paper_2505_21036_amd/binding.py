@@ -12,6 +12,7 @@ import numpy as np
 
 RF_SPATIAL, RF_TEMPORAL, RF_TEXTURAL, RF_DENSE = 0, 1, 2, 3
 RF_SAMPLE_FIRST_FRAME, RF_SAMPLE_EQUAL_INTERVAL = 0, 1
+RF_FLAG_TWO_HEAD = 1
 RF_PLAN_PARTIAL = 0x40000000
 RF_KEY_TILE = 64
 
@@ -32,11 +33,11 @@ class rf_layout(C.Structure):
 
 class rf_params(C.Structure):
     _fields_ = [("bw_spatial", C.c_float), ("bw_temporal", C.c_float), ("tex_stride", C.c_int32),
-                ("sample_interval", C.c_int32)]
+                ("sample_interval", C.c_int32), ("flags", C.c_int32)]
 
     @classmethod
     def default(cls):
-        return cls(0.25, 0.25, 2, 0)
+        return cls(0.25, 0.25, 2, 0, 0)
 
 
 def library_path():

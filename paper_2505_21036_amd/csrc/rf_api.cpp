@@ -182,7 +182,7 @@ size_t rf_arm_workspace_bytes(int B, int nH, const rf_layout* layout, const rf_p
 
 // Geometry of `params` with both band widths replaced by bw.
 static int geometry_with_bandwidth(const rf_layout* layout, const rf_params* params, float bw, Geometry* g) {
-    rf_params p = params ? *params : rf_params{0.25f, 0.25f, 2, 0};
+    rf_params p = params ? *params : rf_params{0.25f, 0.25f, 2, 0, 0};
     p.bw_spatial = bw;
     p.bw_temporal = bw;
     return resolve_geometry(layout, &p, g);
@@ -249,6 +249,7 @@ static int arm_classify_impl(const void* Q, const void* K, int B, int nH, int D,
     a.row_recall = static_cast<float*>(workspace);
     a.max_n = static_cast<int>(arm_rows(g));
     a.threshold = threshold;
+    a.fallback_class = g.two_head ? RF_DENSE : RF_TEXTURAL;
     a.head_class = head_class;
     a.head_bw = head_bw;
     a.recalls = recalls;

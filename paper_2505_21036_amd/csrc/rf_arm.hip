@@ -142,7 +142,7 @@ __global__ void __launch_bounds__(256) arm_finish_kernel(ArmArgs a) {
             __syncthreads();
         }
     if (tid == 0) {
-        int cls = RF_TEXTURAL, chosen = -1;
+        int cls = a.fallback_class, chosen = -1;
         for (int pass = 0; pass < 2 && chosen < 0; ++pass)  // Temporal (pass 0) has priority
             for (int i = 0; i < n_bw && chosen < 0; ++i) {
                 const int b = a.by_width[i];

@@ -23,6 +23,7 @@ struct Geometry {
     int r_spatial, r_temporal;  // band half-widths in frames / in-frame positions
     int tau;                    // checkerboard stride (Eq. 4)
     int omega;                  // global sampling interval (Sec. 3.3)
+    int two_head;               // ARM fallback class is DENSE instead of TEXTURAL
 };
 
 // Host copy of everything the attention kernel needs besides the tensors.
@@ -100,6 +101,7 @@ struct ArmArgs {
     float* row_recall; // device [BH][2][n_bw][max_n]
     int max_n;
     float threshold;
+    int fallback_class;   // class of a head that matches neither mask
     int32_t* head_class;  // device [BH]
     int32_t* head_bw;     // device [BH] or null: chosen candidate index, -1 for Textural heads
     float* recalls;       // device [BH][2][n_bw] or null

@@ -27,17 +27,19 @@ int resolve_geometry(const rf_layout* L, const rf_params* P, Geometry* g) {
     const int64_t Nv = HW * L->T;
     const int64_t N = Nv + L->text_len;
     if (N > (int64_t{1} << 24)) return RF_ERR_SHAPE;  // keeps every index and block count in int32
-    rf_params def = {0.25f, 0.25f, 2, 0};
+    rf_params def = {0.25f, 0.25f, 2, 0, 0};
     const rf_params* p = P ? P : &def;
     if (!(p->bw_spatial >= 0.f && p->bw_spatial <= 1.f)) return RF_ERR_PARAM;
     if (!(p->bw_temporal >= 0.f && p->bw_temporal <= 1.f)) return RF_ERR_PARAM;
     if (p->tex_stride < 1 || p->sample_interval < 0) return RF_ERR_PARAM;
+    if (p->flags & ~RF_FLAG_TWO_HEAD) return RF_ERR_PARAM;
     g->T = L->T; g->H = L->H; g->W = L->W; g->text_len = L->text_len;
     g->HW = static_cast<int>(HW); g->Nv = static_cast<int>(Nv); g->N = static_cast<int>(N);
     g->r_spatial = band_radius(p->bw_spatial, L->T);
     g->r_temporal = band_radius(p->bw_temporal, g->HW);
     g->tau = p->tex_stride;
     g->omega = p->sample_interval > 0 ? p->sample_interval : L->T;
+    g->two_head = (p->flags & RF_FLAG_TWO_HEAD) ? 1 : 0;
     return RF_OK;
 }
 

@@ -28,8 +28,9 @@ def lay(w):
     return rf.rf_layout(w.T, w.H, w.W, w.text_len), orc.Layout(w.T, w.H, w.W, w.text_len)
 
 
-def par(bs=0.25, bt=0.25, tau=2, omega=0):
-    return rf.rf_params(bs, bt, tau, omega), orc.Params(bs, bt, tau, omega)
+def par(bs=0.25, bt=0.25, tau=2, omega=0, two_head=False):
+    return (rf.rf_params(bs, bt, tau, omega, rf.RF_FLAG_TWO_HEAD if two_head else 0),
+            orc.Params(bs, bt, tau, omega, two_head))
 
 
 def f32(t):
@@ -173,6 +174,8 @@ def test_arm_small_shapes(name, mode):
     for alpha in (0.3, 0.5, 0.9):
         arm_compare(w, Q, K, mode, alpha, *par())
     arm_compare(w, Q, K, mode, 0.5, *par(0.1, 0.4, 2, 3))  # other bandwidths, sampling interval 3
+    hc, _ = arm_compare(w, Q, K, mode, 0.9, *par(two_head=True))  # i.i.d. heads match no mask at 0.9
+    assert (hc == rf.RF_DENSE).all()
 
 
 def test_arm_recovers_planted_structure():

@@ -364,3 +364,15 @@ def test_plus_recalls_grow_with_bandwidth_and_minimum_is_chosen():
     # candidate order must not matter
     c, idx, _ = orc.arm_classify_plus(q, k, L, Params(), orc.SAMPLE_FIRST_FRAME, 0.4, (0.125, 0.5, 0.25))
     assert (c, idx) == (TEMPORAL, 2)
+
+
+def test_two_head_mode_sends_unmatched_heads_to_dense():
+    """Tab. 2 "two mask" rows: without the Textural pattern a head that matches neither mask stays dense."""
+    L = Layout(4, 4, 4)
+    q, k, _ = rand_head(64, 8, 40, 3.0)
+    for alpha in (0.2, 0.6, 0.99):
+        c3, r3 = orc.arm_classify(q, k, L, Params(), orc.SAMPLE_FIRST_FRAME, alpha)
+        c2, r2 = orc.arm_classify(q, k, L, Params(two_head=True), orc.SAMPLE_FIRST_FRAME, alpha)
+        assert r2 == r3 and c2 == (DENSE if c3 == TEXTURAL else c3)
+    c2, idx, _ = orc.arm_classify_plus(q, k, L, Params(two_head=True), orc.SAMPLE_FIRST_FRAME, 0.999, BWS)
+    assert (c2, idx) == (DENSE, -1)
