@@ -212,7 +212,8 @@ def main():
     def executed(classes):
         tot = 0
         for c in set(classes):
-            vis, _, _ = rf.plan_block_counts(rl, None, block, c)
+            # Temporal heads walk the position-major copy (the workspace is always given here)
+            vis, _, _ = rf.plan_block_counts(rl, None, block, rf.RF_LIST_TEMPORAL_POSITION_MAJOR if c == 1 else c)
             tot += vis * classes.count(c)
         return per_pair * block * rf.RF_KEY_TILE * tot
 

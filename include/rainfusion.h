@@ -123,10 +123,12 @@ int rf_arm_classify_plus(const void *Q, const void *K, int B, int nH, int D, con
  *               Values outside 0..3 are treated as RF_DENSE.
  * O           : device, bf16 [B, nH, N, D], written.
  * workspace   : optional device scratch of at least rf_attention_workspace_bytes() bytes, 16-byte
- *               aligned.  If given, the kept keys and values of every Textural head are first packed
- *               into it (K_C, V_C of Eq. 5 made contiguous), which is faster than the default of
- *               gathering their rows through an index table; the result is the same.  NULL: no
- *               packing.  Contents undefined afterwards; overlapping calls need separate workspaces.
+ *               aligned.  If given, K and V of the heads that profit are first copied into it in a
+ *               friendlier order: the kept keys of Textural heads made contiguous (K_C, V_C of Eq. 5),
+ *               the tokens of Temporal heads in position-major order (same in-frame position of all
+ *               frames adjacent), where the Temporal band is one contiguous run of keys per query
+ *               block.  The result is the same as without it.  NULL: no copies.  Contents undefined
+ *               afterwards; overlapping calls need separate workspaces.
  */
 int rf_sparse_attention(const void *Q, const void *K, const void *V, const int32_t *head_class, int B,
                         int nH, int D, const rf_layout *layout, const rf_params *params, int block,
@@ -144,7 +146,7 @@ int rf_sparse_attention_plus(const void *Q, const void *K, const void *V, const 
                              const rf_layout *layout, const rf_params *params, int block, void *O,
                              void *workspace, size_t workspace_bytes, void *stream);
 
-/* Bytes of the optional workspace of rf_sparse_attention (room for K_C and V_C of every head);
+/* Bytes of the optional workspace of rf_sparse_attention (room for a copy of K and V);
  * 0 if the arguments are invalid. */
 size_t rf_attention_workspace_bytes(int B, int nH, int D, const rf_layout *layout, const rf_params *params);
 
@@ -158,11 +160,15 @@ size_t rf_attention_workspace_bytes(int B, int nH, int D, const rf_layout *layou
  *             contains a dropped token pair or runs past the last token (the kernel applies the
  *             token predicate there).  For RF_TEXTURAL, query blocks made only of video tokens
  *             index tiles of the COMPACTED key sequence (kept keys in token order, then text).
+ *             cls = RF_LIST_TEMPORAL_POSITION_MAJOR gives the list a Temporal head walks when a
+ *             workspace is given: query blocks and key tiles are then runs of the position-major
+ *             order (see rf_plan_position_major).
  *   needed  : host, receives the number of entries.
  * Returns RF_ERR_WORKSPACE if cap < *needed (nothing but *needed and row_ptr is written then).
  */
 #define RF_PLAN_PARTIAL 0x40000000
 #define RF_KEY_TILE 64
+#define RF_LIST_TEMPORAL_POSITION_MAJOR 4
 int rf_plan_host(const rf_layout *layout, const rf_params *params, int block, int cls,
                  int32_t *row_ptr, int32_t *cols, size_t cap, size_t *needed);
 
@@ -173,6 +179,11 @@ int rf_plan_host(const rf_layout *layout, const rf_params *params, int block, in
  * RF_DENSE heads use the identity.
  */
 int rf_plan_order(const rf_layout *layout, const rf_params *params, int block, int cls, int32_t *order);
+
+/* Position-major order of the tokens: token_of (host, int32 [N]) receives, for every row of that
+ * order, the token it holds: video token (frame f, in-frame position p) is row p*T + f, text
+ * tokens keep their place after the video tokens. */
+int rf_plan_position_major(const rf_layout *layout, int32_t *token_of);
 
 /* Drop every cached block list and free its device memory (synchronises the device). */
 int rf_plan_clear(void);

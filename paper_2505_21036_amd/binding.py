@@ -15,6 +15,7 @@ RF_SAMPLE_FIRST_FRAME, RF_SAMPLE_EQUAL_INTERVAL = 0, 1
 RF_FLAG_TWO_HEAD = 1
 RF_PLAN_PARTIAL = 0x40000000
 RF_KEY_TILE = 64
+RF_LIST_TEMPORAL_POSITION_MAJOR = 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("RF_LIBRARY") or os.path.join(_HERE, "librainfusion.so")
@@ -79,6 +80,8 @@ def load_library():
     lib.rf_plan_host.argtypes = [PL, PP, C.c_int, C.c_int, vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
     lib.rf_plan_order.restype = C.c_int
     lib.rf_plan_order.argtypes = [PL, PP, C.c_int, C.c_int, vp]
+    lib.rf_plan_position_major.restype = C.c_int
+    lib.rf_plan_position_major.argtypes = [PL, vp]
     lib.rf_plan_clear.restype = C.c_int
     lib.rf_plan_clear.argtypes = []
     _lib = lib
@@ -247,6 +250,16 @@ def rf_plan_order(layout, params, block, cls):
     if st != 0:
         raise RfError(st, "rf_plan_order")
     return order
+
+
+def rf_plan_position_major(layout):
+    """token_of[row] for the position-major order of the tokens (int32 [N])."""
+    N = layout.T * layout.H * layout.W + layout.text_len
+    out = np.full(N, -1, dtype=np.int32)
+    st = load_library().rf_plan_position_major(C.byref(layout), out.ctypes.data)
+    if st != 0:
+        raise RfError(st, "rf_plan_position_major")
+    return out
 
 
 def plan_block_counts(layout, params, block, cls):

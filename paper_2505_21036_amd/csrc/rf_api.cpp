@@ -69,14 +69,14 @@ int get_attention_plan(const Geometry& g, int block, const DevicePlan** out) {
         HostPlan hp;
         build_plan(g, block, &hp);
         BlobBuilder bb;
-        size_t off_rp[3], off_co[3], off_at[3], off_qo[3];
-        for (int c = 0; c < 3; ++c) {
+        size_t off_rp[kLists], off_co[kLists], off_at[kLists], off_qo[kLists];
+        for (int c = 0; c < kLists; ++c) {
             off_rp[c] = bb.add(hp.row_ptr[c]);
             off_co[c] = bb.add(hp.cols[c]);
             off_at[c] = bb.add(hp.attr[c]);
             off_qo[c] = bb.add(hp.qorder[c]);
         }
-        const size_t off_ci = bb.add(hp.cidx);
+        const size_t off_ci = bb.add(hp.cidx), off_pm = bb.add(hp.pm_token);
         auto p = std::make_unique<CachedPlan>();
         p->g = g;
         p->block = block;
@@ -85,16 +85,18 @@ int get_attention_plan(const Geometry& g, int block, const DevicePlan** out) {
         if (st != RF_OK) return st;
         const int32_t* base = static_cast<const int32_t*>(p->blob);
         DevicePlan& d = p->dev;
-        for (int c = 0; c < 3; ++c) {
+        for (int c = 0; c < kLists; ++c) {
             d.row_ptr[c] = base + off_rp[c];
             d.cols[c] = base + off_co[c];
             d.attr[c] = base + off_at[c];
             d.qorder[c] = base + off_qo[c];
         }
         d.cidx = base + off_ci;
+        d.pm_token = base + off_pm;
         d.radius[RF_SPATIAL] = g.r_spatial;
         d.radius[RF_TEMPORAL] = g.r_temporal;
         d.radius[RF_TEXTURAL] = 0;
+        d.radius[kListTemporalPM] = g.r_temporal;
         d.N = g.N; d.Nv = g.Nv; d.Nc = hp.Nc;
         d.block = block; d.nQB = hp.nQB; d.nKT = hp.nKT; d.nCT = hp.nCT;
         d.first_text_qb = hp.first_text_qb;
@@ -274,17 +276,10 @@ int rf_arm_classify_plus(const void* Q, const void* K, int B, int nH, int D, con
                              head_bw, recalls, workspace, workspace_bytes, stream);
 }
 
-static size_t packed_count(const Geometry& g) {
-    int64_t kept = 0;
-    for (int y = 0; y < g.H; ++y)
-        for (int x = 0; x < g.W; ++x) kept += ((y - x) % g.tau) == 0;
-    return static_cast<size_t>(kept * g.T + g.text_len);
-}
-
 size_t rf_attention_workspace_bytes(int B, int nH, int D, const rf_layout* layout, const rf_params* params) {
     Geometry g;
     if (resolve_geometry(layout, params, &g) != RF_OK || check_shape(B, nH, D, g) != RF_OK) return 0;
-    return 2 * static_cast<size_t>(B) * nH * packed_count(g) * D * sizeof(uint16_t);
+    return 2 * static_cast<size_t>(B) * nH * g.N * D * sizeof(uint16_t);
 }
 
 static int sparse_attention_impl(const void* Q, const void* K, const void* V, const int32_t* head_class,
@@ -324,7 +319,7 @@ static int sparse_attention_impl(const void* Q, const void* K, const void* V, co
     a.scale_log2 = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(D)));
     if (workspace) {
         a.packed_k = static_cast<uint16_t*>(workspace);
-        a.packed_v = a.packed_k + static_cast<size_t>(B) * nH * a.plan[0].Nc * D;
+        a.packed_v = a.packed_k + static_cast<size_t>(B) * nH * g.N * D;
         if (launch_pack_textural(a, D, stream) != 0) return RF_ERR_HIP;
     }
     return launch_attention(a, D, stream) == 0 ? RF_OK : RF_ERR_HIP;
@@ -355,7 +350,7 @@ int rf_plan_host(const rf_layout* layout, const rf_params* params, int block, in
     const int st = resolve_geometry(layout, params, &g);
     if (st != RF_OK) return st;
     if (block != 64 && block != 128) return RF_ERR_BLOCK;
-    if (cls < RF_SPATIAL || cls > RF_DENSE) return RF_ERR_PARAM;
+    if (cls < RF_SPATIAL || cls > RF_LIST_TEMPORAL_POSITION_MAJOR) return RF_ERR_PARAM;
     HostPlan hp;
     build_plan(g, block, &hp);
     std::vector<int32_t> rp, co;
@@ -375,10 +370,21 @@ int rf_plan_order(const rf_layout* layout, const rf_params* params, int block, i
     const int st = resolve_geometry(layout, params, &g);
     if (st != RF_OK) return st;
     if (block != 64 && block != 128) return RF_ERR_BLOCK;
-    if (cls < RF_SPATIAL || cls > RF_DENSE) return RF_ERR_PARAM;
+    if (cls < RF_SPATIAL || cls > RF_LIST_TEMPORAL_POSITION_MAJOR) return RF_ERR_PARAM;
     HostPlan hp;
     build_plan(g, block, &hp);
-    for (int i = 0; i < hp.nQB; ++i) order[i] = cls == RF_DENSE ? i : hp.qorder[cls][i];
+    const int list = cls == RF_LIST_TEMPORAL_POSITION_MAJOR ? kListTemporalPM : cls;
+    for (int i = 0; i < hp.nQB; ++i) order[i] = cls == RF_DENSE ? i : hp.qorder[list][i];
+    return RF_OK;
+}
+
+int rf_plan_position_major(const rf_layout* layout, int32_t* token_of) {
+    if (!layout || !token_of) return RF_ERR_NULL;
+    Geometry g;
+    const int st = resolve_geometry(layout, nullptr, &g);
+    if (st != RF_OK) return st;
+    for (int n = 0; n < g.Nv; ++n) token_of[n] = (n % g.T) * g.HW + n / g.T;
+    for (int n = g.Nv; n < g.N; ++n) token_of[n] = n;
     return RF_OK;
 }
 

@@ -175,6 +175,8 @@ struct AttnSmem {
 
 struct QueryBlock {
     int bh, qb, cls;
+    int list;                    // MODE_LISTED: which of the plan's lists (a class, or Temporal position-major)
+    const int32_t* row_token;    // null, or: row of the walked order -> token (queries are gathered, O scattered)
     const unsigned char* kbase;  // K and V rows of the key sequence walked (the head's, or its compacted copy)
     const unsigned char* vbase;
     const int32_t* cols;  // MODE_LISTED: this query block's tile entries
@@ -195,7 +197,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
     const int N = pl.N, Nv = pl.Nv, keyN = qk.keyN, ntiles = qk.ntiles;
     // per-key side data staged through LDS two tiles ahead: the token index of each key of the
     // compacted sequence, or the pattern attribute (frame / position / kept flag) of each key
-    const int32_t* side_src = MODE == MODE_COMPACT ? pl.cidx : (MODE == MODE_LISTED ? pl.attr[qk.cls] : nullptr);
+    const int32_t* side_src = MODE == MODE_COMPACT ? pl.cidx : (MODE == MODE_LISTED ? pl.attr[qk.list] : nullptr);
     int* side = reinterpret_cast<int*>(smem + SM::SIDE_OFF);
 
     const unsigned char* Kh = qk.kbase;
@@ -203,16 +205,17 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
     const uint16_t* Qh = a.Q + static_cast<size_t>(qk.bh) * N * D;
 
     // this lane's query
-    const int qrow = qk.qb * BQ + wave * 32 + m;
-    const int qtok = min(qrow, N - 1);
+    const int qrow = qk.qb * BQ + wave * 32 + m;  // row of the walked order
+    const int qrow_c = min(qrow, N - 1);
+    const int qtok = (MODE == MODE_LISTED && qk.row_token) ? qk.row_token[qrow_c] : qrow_c;
     bf16x8 qf[D / 16];
     load_q_frags<D>(Qh, qtok, hf, qf);
     int q_attr = 0, q_rad = 0x3fffffff;  // text queries keep everything
     if (MODE == MODE_LISTED) {
         // Spatial / Temporal compare the query's frame / position with the key's; the Textural
         // table is 0 on kept keys and 1 on dropped ones, compared against 0 with radius 0
-        if (qk.cls != RF_TEXTURAL) q_attr = side_src[qtok];
-        if (qtok < Nv) q_rad = pl.radius[qk.cls];
+        if (qk.cls != RF_TEXTURAL) q_attr = side_src[qrow_c];
+        if (qrow_c < Nv) q_rad = pl.radius[qk.list];
     }
     const uint32_t q_lo = static_cast<uint32_t>(q_rad - q_attr), q_span = 2u * static_cast<uint32_t>(q_rad);
 
@@ -439,7 +442,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
     const float l_tot = l_run + other_half(l_run);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     if (qrow < N) {
-        uint16_t* orow = a.O + static_cast<size_t>(qk.bh) * N * D + static_cast<size_t>(qrow) * D;
+        uint16_t* orow = a.O + static_cast<size_t>(qk.bh) * N * D + static_cast<size_t>(qtok) * D;
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -480,8 +483,13 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
     int cls = a.head_class[qk.bh];
     if (static_cast<unsigned>(cls) > 3u) cls = RF_DENSE;
     qk.cls = cls;
-    qk.qb = cls == RF_DENSE ? ordinal : pl.qorder[cls][ordinal];
+    // a Temporal head walks the position-major copy of its K and V if the caller gave room for one
+    const bool temporal_pm = cls == RF_TEMPORAL && a.packed_k;
+    const int list = temporal_pm ? kListTemporalPM : cls;
+    qk.qb = cls == RF_DENSE ? ordinal : pl.qorder[list][ordinal];
     qk.cols = nullptr;
+    qk.list = cls;
+    qk.row_token = nullptr;
     const size_t head_bytes = static_cast<size_t>(qk.bh) * pl.N * D * 2;
     qk.kbase = reinterpret_cast<const unsigned char*>(a.K) + head_bytes;
     qk.vbase = reinterpret_cast<const unsigned char*>(a.V) + head_bytes;
@@ -496,7 +504,7 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
         qk.ntiles = pl.nCT;
         qk.keyN = pl.Nc;
         if (a.packed_k) {
-            const size_t packed_bytes = static_cast<size_t>(qk.bh) * pl.Nc * D * 2;
+            const size_t packed_bytes = head_bytes;
             qk.kbase = reinterpret_cast<const unsigned char*>(a.packed_k) + packed_bytes;
             qk.vbase = reinterpret_cast<const unsigned char*>(a.packed_v) + packed_bytes;
             attend<D, NW, MODE_ALL>(a, pl, qk, smem);
@@ -504,28 +512,37 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
             attend<D, NW, MODE_COMPACT>(a, pl, qk, smem);
         }
     } else {
-        const int e0 = pl.row_ptr[cls][qk.qb];
-        qk.ntiles = pl.row_ptr[cls][qk.qb + 1] - e0;
-        qk.cols = pl.cols[cls] + e0;
+        qk.list = list;
+        if (temporal_pm) {
+            qk.row_token = pl.pm_token;
+            qk.kbase = reinterpret_cast<const unsigned char*>(a.packed_k) + head_bytes;
+            qk.vbase = reinterpret_cast<const unsigned char*>(a.packed_v) + head_bytes;
+        }
+        const int e0 = pl.row_ptr[list][qk.qb];
+        qk.ntiles = pl.row_ptr[list][qk.qb + 1] - e0;
+        qk.cols = pl.cols[list] + e0;
         qk.keyN = pl.N;
         attend<D, NW, MODE_LISTED>(a, pl, qk, smem);
     }
 }
 
-// K_C, V_C of Eq. 5 made physical: for every Textural head, the kept keys' rows (then the text
-// rows) copied in order into the caller's workspace.  One workgroup per (64 packed rows, head).
+// Copies of K and V in the order their head walks them, into the caller's workspace: for a
+// Textural head the kept keys' rows, then the text rows (K_C, V_C of Eq. 5 made physical); for a
+// Temporal head every row, in position-major order.  One workgroup per (64 copied rows, head).
 template <int D>
 __global__ void __launch_bounds__(256) pack_textural_kernel(AttnArgs a) {
     const DevicePlan& pl = a.plan[0];
-    const int bh = blockIdx.y;
-    if (a.head_class[bh] != RF_TEXTURAL) return;
+    const int bh = blockIdx.y, cls = a.head_class[bh];
+    if (cls != RF_TEXTURAL && cls != RF_TEMPORAL) return;
+    const int32_t* token_of = cls == RF_TEXTURAL ? pl.cidx : pl.pm_token;
+    const int rows = cls == RF_TEXTURAL ? pl.Nc : pl.N;
     constexpr int CH = D / 8;  // 16-byte chunks per row
-    const size_t src_head = static_cast<size_t>(bh) * pl.N * D, dst_head = static_cast<size_t>(bh) * pl.Nc * D;
+    const size_t head = static_cast<size_t>(bh) * pl.N * D;
     for (int i = threadIdx.x; i < kTileK * CH; i += 256) {
         const int c = blockIdx.x * kTileK + i / CH, ch = i % CH;
-        if (c >= pl.Nc) break;
-        const size_t src = src_head + static_cast<size_t>(pl.cidx[c]) * D + 8 * ch;
-        const size_t dst = dst_head + static_cast<size_t>(c) * D + 8 * ch;
+        if (c >= rows) break;
+        const size_t src = head + static_cast<size_t>(token_of[c]) * D + 8 * ch;
+        const size_t dst = head + static_cast<size_t>(c) * D + 8 * ch;
         *reinterpret_cast<u32x4*>(a.packed_k + dst) = *reinterpret_cast<const u32x4*>(a.K + src);
         *reinterpret_cast<u32x4*>(a.packed_v + dst) = *reinterpret_cast<const u32x4*>(a.V + src);
     }
@@ -533,7 +550,7 @@ __global__ void __launch_bounds__(256) pack_textural_kernel(AttnArgs a) {
 
 int launch_pack_textural(const AttnArgs& a, int D, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const dim3 grid(a.plan[0].nCT, a.BH);
+    const dim3 grid(a.plan[0].nKT, a.BH);
     if (D == 64) hipLaunchKernelGGL(pack_textural_kernel<64>, grid, dim3(256), 0, st, a);
     else if (D == 96) hipLaunchKernelGGL(pack_textural_kernel<96>, grid, dim3(256), 0, st, a);
     else if (D == 128) hipLaunchKernelGGL(pack_textural_kernel<128>, grid, dim3(256), 0, st, a);

@@ -26,8 +26,13 @@ struct Geometry {
     int two_head;               // ARM fallback class is DENSE instead of TEXTURAL
 };
 
+// Lists: 0/1/2 = Spatial / Temporal / Textural in token order; 3 = Temporal in POSITION-MAJOR
+// order (video token (frame f, position p) sits at p*T + f, text tokens stay last), where the
+// Temporal band |p_i - p_j| <= r is one contiguous run of keys per query block.
+constexpr int kLists = 4;
+constexpr int kListTemporalPM = 3;
+
 // Host copy of everything the attention kernel needs besides the tensors.
-// Index 0/1/2 of the per-class arrays = Spatial / Temporal / Textural.
 struct HostPlan {
     Geometry g;
     int block;     // query rows per block (64 or 128) = rows one workgroup owns
@@ -37,10 +42,12 @@ struct HostPlan {
     int nCT;       // ceil(Nc / kTileK): key tiles of the compacted sequence
     int first_text_qb;  // first query block holding a text row (nQB if there is none)
     // CSR lists of key tiles per query block; Textural: text-holding query blocks only
-    std::vector<int32_t> row_ptr[3], cols[3];
-    std::vector<int32_t> qorder[3];  // order in which a head's query blocks are handed out (a permutation)
-    std::vector<int32_t> attr[3];  // per token: frame index / in-frame index / 0 if kept by Eq. 4 else 1
-    std::vector<int32_t> cidx;     // compacted position -> token index (Textural)
+    std::vector<int32_t> row_ptr[kLists], cols[kLists];
+    std::vector<int32_t> qorder[kLists];  // order in which a head's query blocks are handed out (a permutation)
+    // per row of the list's order: frame index / in-frame index / 0 if kept by Eq. 4 else 1 / in-frame index
+    std::vector<int32_t> attr[kLists];
+    std::vector<int32_t> cidx;      // compacted position -> token index (Textural)
+    std::vector<int32_t> pm_token;  // position-major row -> token index
 };
 
 // Fills g from layout/params (params may be null -> paper defaults). Returns an rf_status.
@@ -54,12 +61,13 @@ void flatten_class(const HostPlan& plan, int cls, std::vector<int32_t>* row_ptr,
 
 // Device-resident plan: raw device pointers into one allocation.
 struct DevicePlan {
-    const int32_t* row_ptr[3];
-    const int32_t* cols[3];
-    const int32_t* attr[3];
-    const int32_t* qorder[3];
+    const int32_t* row_ptr[kLists];
+    const int32_t* cols[kLists];
+    const int32_t* attr[kLists];
+    const int32_t* qorder[kLists];
     const int32_t* cidx;
-    int radius[3];
+    const int32_t* pm_token;
+    int radius[kLists];
     int N, Nv, Nc;
     int block, nQB, nKT, nCT, first_text_qb;
 };
@@ -73,7 +81,8 @@ struct AttnArgs {
     const int32_t* head_class;
     int BH;            // B * nH
     float scale_log2;  // log2(e) / sqrt(D)
-    // optional: compacted K and V of Textural heads, [BH][Nc][D] each (null: gather through the index table)
+    // optional: packed copies of K and V, [BH][N][D] each: the kept rows of Textural heads (first Nc rows),
+    // all rows of Temporal heads in position-major order; null: no packing
     uint16_t* packed_k;
     uint16_t* packed_v;
     const int32_t* head_bw;  // optional per-head index into plan[]; null or out of range: plan[0]

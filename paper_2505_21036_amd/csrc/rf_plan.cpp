@@ -76,7 +76,7 @@ static void order_query_blocks(HostPlan* plan) {
     const int nQB = P.nQB, block = P.block, HW = P.g.HW, Nv = P.g.Nv;
     const int per_share = (nQB + 7) / 8;
     constexpr int kRunBlocks = 8;
-    for (int cls = 0; cls < 3; ++cls) {
+    for (int cls = 0; cls < kLists; ++cls) {
         std::vector<int32_t> ord(nQB);
         for (int qb = 0; qb < nQB; ++qb) ord[qb] = qb;
         if (cls == RF_TEMPORAL) {
@@ -141,6 +141,13 @@ void build_plan(const Geometry& g, int block, HostPlan* plan) {
     // per-token attributes
     for (auto& a : P.attr) a.assign(N, 0);
     P.cidx.clear();
+    P.pm_token.resize(N);
+    for (int n = 0; n < Nv; ++n) {  // position-major row n = p*T + f
+        const int p = n / g.T, f = n % g.T;
+        P.pm_token[n] = f * HW + p;
+        P.attr[kListTemporalPM][n] = p;
+    }
+    for (int n = Nv; n < N; ++n) P.pm_token[n] = n;
     for (int n = 0; n < Nv; ++n) {
         const int f = n / HW, p = n % HW, y = p / g.W, x = p % g.W;
         P.attr[RF_SPATIAL][n] = f;
@@ -154,7 +161,11 @@ void build_plan(const Geometry& g, int block, HostPlan* plan) {
     P.nCT = (P.Nc + kTileK - 1) / kTileK;
 
     std::vector<Span> qs, ks;
-    for (int cls = 0; cls < 3; ++cls) {
+    for (int cls = 0; cls < kLists; ++cls) {
+        // a band over groups of consecutive rows: frames of HW tokens (Spatial), positions of T tokens
+        // (Temporal in position-major order)
+        const bool banded = cls == RF_SPATIAL || cls == kListTemporalPM;
+        const int group = cls == RF_SPATIAL ? HW : g.T, group_radius = cls == RF_SPATIAL ? g.r_spatial : g.r_temporal;
         auto& rp = P.row_ptr[cls];
         auto& co = P.cols[cls];
         rp.assign(P.nQB + 1, 0);
@@ -171,10 +182,10 @@ void build_plan(const Geometry& g, int block, HostPlan* plan) {
                 const bool k_text = k1 > Nv, k_video = k0 < Nv;
                 bool any = q_text || k_text, all = true;
                 if (q_video && k_video) {
-                    if (cls == RF_SPATIAL) {
-                        Span a{q0 / HW, (qv1 - 1) / HW}, b{k0 / HW, (kv1 - 1) / HW};
-                        any = any || span_gap(a, b) <= g.r_spatial;
-                        all = span_reach(a, b) <= g.r_spatial;
+                    if (banded) {
+                        Span a{q0 / group, (qv1 - 1) / group}, b{k0 / group, (kv1 - 1) / group};
+                        any = any || span_gap(a, b) <= group_radius;
+                        all = span_reach(a, b) <= group_radius;
                     } else if (cls == RF_TEMPORAL) {
                         position_spans(k0, kv1, HW, &ks);
                         for (Span a : qs)
@@ -206,7 +217,9 @@ void build_plan(const Geometry& g, int block, HostPlan* plan) {
     order_query_blocks(plan);
 }
 
+// cls in the public numbering: a head class, or RF_LIST_TEMPORAL_POSITION_MAJOR
 void flatten_class(const HostPlan& P, int cls, std::vector<int32_t>* row_ptr, std::vector<int32_t>* cols) {
+    const int list = cls == RF_LIST_TEMPORAL_POSITION_MAJOR ? kListTemporalPM : cls;
     row_ptr->assign(P.nQB + 1, 0);
     cols->clear();
     for (int qb = 0; qb < P.nQB; ++qb) {
@@ -216,8 +229,8 @@ void flatten_class(const HostPlan& P, int cls, std::vector<int32_t>* row_ptr, st
             for (int kt = 0; kt < nt; ++kt)
                 cols->push_back(kt | ((kt + 1) * kTileK > len ? RF_PLAN_PARTIAL : 0));
         } else {
-            for (int e = P.row_ptr[cls][qb]; e < P.row_ptr[cls][qb + 1]; ++e)
-                cols->push_back(P.cols[cls][e] & ~kTileBoundary);
+            for (int e = P.row_ptr[list][qb]; e < P.row_ptr[list][qb + 1]; ++e)
+                cols->push_back(P.cols[list][e] & ~kTileBoundary);
         }
         (*row_ptr)[qb + 1] = static_cast<int32_t>(cols->size());
     }

@@ -52,7 +52,7 @@ def run_attention(w, Q, K, V, classes, block, params=None, packed=False):
     rl, _ = lay(w)
     hc = torch.as_tensor(classes, dtype=torch.int32).reshape(w.B, w.nH).to(DEV)
     ws = None
-    if packed:  # pack K_C, V_C of Textural heads into a caller-provided workspace first
+    if packed:  # Textural heads pack K_C, V_C, Temporal heads a position-major copy, into this workspace first
         ws = torch.empty(rf.rf_attention_workspace_bytes(w.B, w.nH, w.D, rl, params), dtype=torch.uint8, device=DEV)
     O = rf.rf_sparse_attention(Q, K, V, hc, rl, params, block, workspace=ws)
     torch.cuda.synchronize()
@@ -71,8 +71,8 @@ def test_small_shapes_every_class_every_row(name, block, scale):
     rp, op = par()
     _, ol = lay(w)
     Q, K, V = inp.full_qkv(w, DEV, scale)
-    for cls, packed in ((rf.RF_SPATIAL, False), (rf.RF_TEMPORAL, False), (rf.RF_TEXTURAL, False),
-                        (rf.RF_TEXTURAL, True), (rf.RF_DENSE, False)):
+    for cls, packed in ((rf.RF_SPATIAL, False), (rf.RF_TEMPORAL, False), (rf.RF_TEMPORAL, True),
+                        (rf.RF_TEXTURAL, False), (rf.RF_TEXTURAL, True), (rf.RF_DENSE, False)):
         O = run_attention(w, Q, K, V, [cls] * (w.B * w.nH), block, rp, packed)
         for b in range(w.B):
             for h in range(w.nH):
@@ -307,6 +307,8 @@ def test_hunyuan720p_headline_layer():
     classes = inp.thirds_classes(w).flatten().tolist()
     O = run_attention(w, Q, K, V, classes, w.block)
     sampled_parity(w, O, classes, [(0, 0), (0, 8), (0, 16)], 20, tag="thirds")
+    O = run_attention(w, Q, K, V, classes, w.block, packed=True)
+    sampled_parity(w, O, classes, [(0, 9), (0, 15), (0, 17)], 20, tag="thirds, packed")
     O = run_attention(w, Q, K, V, hc.flatten().tolist(), w.block, packed=True)  # as bench.py runs it
     sampled_parity(w, O, hc.flatten().tolist(), [(0, 5)], 12, tag="arm-chosen, packed")
     O = run_attention(w, Q, K, V, hc.flatten().tolist(), w.block)

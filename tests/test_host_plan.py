@@ -66,6 +66,33 @@ def test_block_lists_match_brute_force(lay, par, block):
 
 
 @pytest.mark.parametrize("lay", LAYOUTS)
+@pytest.mark.parametrize("par", PARAMS)
+@pytest.mark.parametrize("block", [64, 128])
+def test_position_major_temporal_lists(lay, par, block):
+    """The list a Temporal head walks over the position-major copy: the oracle's mask, rows and
+    columns permuted into that order, scanned by brute force."""
+    L, P = orc.Layout(*lay), orc.Params(par[0], par[1], par[2])
+    rl, rp = rf.rf_layout(*lay), rf.rf_params(par[0], par[1], par[2], 0)
+    N, (T, H, W, tl) = orc.num_tokens(L), lay
+    tok = rf.rf_plan_position_major(rl)
+    assert sorted(tok.tolist()) == list(range(N))
+    for f in range(T):
+        for p in (0, H * W // 2, H * W - 1):
+            assert tok[p * T + f] == f * H * W + p
+    assert (tok[T * H * W:] == np.arange(T * H * W, N)).all()
+    M = orc.keep_matrix(orc.TEMPORAL, L, P)[np.ix_(tok, tok)]
+    any_, full = brute_blocks(M, block)
+    row_ptr, cols = rf.rf_plan_host(rl, rp, block, rf.RF_LIST_TEMPORAL_POSITION_MAJOR)
+    for qb in range(len(row_ptr) - 1):
+        ent = cols[row_ptr[qb]:row_ptr[qb + 1]]
+        kbs, partial = ent & ~rf.RF_PLAN_PARTIAL, (ent & rf.RF_PLAN_PARTIAL) != 0
+        assert set(kbs.tolist()) == set(np.nonzero(any_[qb])[0].tolist())
+        assert (partial == ~full[qb, kbs]).all()
+    order = rf.rf_plan_order(rl, rp, block, rf.RF_LIST_TEMPORAL_POSITION_MAJOR)
+    assert sorted(order.tolist()) == list(range(len(row_ptr) - 1))
+
+
+@pytest.mark.parametrize("lay", LAYOUTS)
 @pytest.mark.parametrize("tau", [1, 2, 3])
 @pytest.mark.parametrize("block", [64, 128])
 def test_textural_lists(lay, tau, block):
@@ -130,7 +157,7 @@ def test_every_declared_symbol_is_exported():
     names = re.findall(r"\b(rf_[a-z_]+)\s*\(", hdr)
     assert set(names) >= {"rf_arm_classify", "rf_sparse_attention", "rf_arm_workspace_bytes", "rf_plan_host",
                           "rf_attention_workspace_bytes", "rf_plan_order", "rf_arm_classify_plus",
-                          "rf_sparse_attention_plus",
+                          "rf_sparse_attention_plus", "rf_plan_position_major",
                           "rf_plan_clear", "rf_status_string", "rf_version"}
     for n in set(names):
         assert getattr(lib, n) is not None
@@ -157,7 +184,7 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     assert attn(par=rf.rf_params(0.25, 0.25, 0, 0)) == -4 and attn(par=rf.rf_params(float("nan"), 0.25, 2, 0)) == -4
     assert attn(block=32) == -5 and attn(block=256) == -5
     need = rf.rf_attention_workspace_bytes(1, 2, 64, L)
-    assert need == 2 * 2 * 128 * 64 * 2  # half of the 256 tokens kept, K and V, 2 heads, bf16
+    assert need == 2 * 2 * 256 * 64 * 2  # a copy of K and of V: 2 heads x 256 tokens x 64 channels, bf16
     assert attn(ws=C.c_void_p(256), wsb=need - 1) == -6 and attn(ws=C.c_void_p(264), wsb=need) == -6
     assert rf.rf_attention_workspace_bytes(1, 2, 80, L) == 0
 
