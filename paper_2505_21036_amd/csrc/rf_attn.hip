@@ -283,14 +283,14 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
     // S^T of tile t (64 keys x this lane's query), predicate applied where the tile is partial
     auto scores = [&](int t, int entry, f32x16 (&s)[2]) {
         const unsigned char* kl = k_lds(t);
+        // the two 32-key halves are independent accumulation chains: alternate them
+        s[0] = f32x16{0};
+        s[1] = f32x16{0};
 #pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2) {
-            f32x16 acc = {0};
+        for (int cc = 0; cc < D / 16; ++cc)
 #pragma unroll
-            for (int cc = 0; cc < D / 16; ++cc)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st.k_frag(kl, kb2, cc), qf[cc], acc, 0, 0, 0);
-            s[kb2] = acc;
-        }
+            for (int kb2 = 0; kb2 < 2; ++kb2)
+                s[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st.k_frag(kl, kb2, cc), qf[cc], s[kb2], 0, 0, 0);
 #ifdef RF_SCHED_QK
         // keep RF_SCHED_QK operand reads in flight ahead of the MFMA that consumes them
         __builtin_amdgcn_sched_group_barrier(0x100, RF_SCHED_QK, 0);
@@ -412,10 +412,11 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
             }
 
         const unsigned char* vl = v_lds(t);
+        // consecutive MFMAs go to different accumulators (channel blocks): no back-to-back dependence
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db)
+        for (int u = 0; u < 4; ++u)
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int db = 0; db < D / 32; ++db)
                 oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st.v_frag(vl, db, u), pf[u], oacc[db], 0, 0, 0);
 #ifdef RF_SCHED_PV
         {
