@@ -65,7 +65,7 @@ enum rf_status {
     RF_ERR_LAYOUT = -3,    /* T, H, W < 1 or text_len < 0 */
     RF_ERR_PARAM = -4,     /* bandwidth outside [0, 1], tex_stride < 1, sample_interval < 0, unknown flags, bad sample_mode,
                               threshold not in [0, 1] or NaN */
-    RF_ERR_BLOCK = -5,     /* block not 64 or 128 */
+    RF_ERR_BLOCK = -5,     /* block not 64, 128 or 256 */
     RF_ERR_WORKSPACE = -6, /* a required workspace is NULL, or a workspace is too small or misaligned */
     RF_ERR_HIP = -7        /* a HIP runtime call failed (allocation, copy or launch) */
 };
@@ -114,7 +114,8 @@ int rf_arm_classify_plus(const void *Q, const void *K, int B, int nH, int D, con
 /*
  * Sparse attention forward, Eq. 1-2 with the mask of each head's pattern (Eq. 3-5):
  *   O[b,h,i,:] = sum_j softmax_j(q_i . k_j / sqrt(D) over kept j) * v_j.
- * The mask is token-level; `block` (64 or 128) is the number of query rows per block, and
+ * The mask is token-level; `block` (64, 128 or 256) is the number of query rows per block (= per
+ * workgroup: larger blocks share each K/V tile among more queries and run faster on long sequences), and
  * (query block, 64-key tile) pairs with no kept token pair are skipped, so O does not
  * depend on it.  Scores and sums are accumulated in fp32, O is rounded to bf16.
  * Q, K, V     : device, bf16 [B, nH, N, D].

@@ -143,6 +143,8 @@ int get_arm_tables(const Geometry& g, const CachedPlan** out) {
     return RF_OK;
 }
 
+bool valid_block(int block) { return block == 64 || block == 128 || block == 256; }  // query rows per block
+
 int check_shape(int B, int nH, int D, const Geometry& g) {
     if (B < 1 || nH < 1) return RF_ERR_SHAPE;
     if (D != 64 && D != 96 && D != 128) return RF_ERR_SHAPE;
@@ -169,7 +171,7 @@ const char* rf_status_string(int status) {
         case RF_ERR_SHAPE: return "bad tensor shape";
         case RF_ERR_LAYOUT: return "bad video layout";
         case RF_ERR_PARAM: return "bad parameter";
-        case RF_ERR_BLOCK: return "block must be 64 or 128";
+        case RF_ERR_BLOCK: return "block must be 64, 128 or 256";
         case RF_ERR_WORKSPACE: return "workspace missing or too small";
         case RF_ERR_HIP: return "HIP runtime error";
         default: return "unknown status";
@@ -292,7 +294,7 @@ static int sparse_attention_impl(const void* Q, const void* K, const void* V, co
     if (st != RF_OK) return st;
     st = check_shape(B, nH, D, g);
     if (st != RF_OK) return st;
-    if (block != 64 && block != 128) return RF_ERR_BLOCK;
+    if (!valid_block(block)) return RF_ERR_BLOCK;
     if (workspace && workspace_bytes < rf_attention_workspace_bytes(B, nH, D, layout, params)) return RF_ERR_WORKSPACE;
     if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 15)) return RF_ERR_WORKSPACE;
 
@@ -349,7 +351,7 @@ int rf_plan_host(const rf_layout* layout, const rf_params* params, int block, in
     Geometry g;
     const int st = resolve_geometry(layout, params, &g);
     if (st != RF_OK) return st;
-    if (block != 64 && block != 128) return RF_ERR_BLOCK;
+    if (!valid_block(block)) return RF_ERR_BLOCK;
     if (cls < RF_SPATIAL || cls > RF_LIST_TEMPORAL_POSITION_MAJOR) return RF_ERR_PARAM;
     HostPlan hp;
     build_plan(g, block, &hp);
@@ -369,7 +371,7 @@ int rf_plan_order(const rf_layout* layout, const rf_params* params, int block, i
     Geometry g;
     const int st = resolve_geometry(layout, params, &g);
     if (st != RF_OK) return st;
-    if (block != 64 && block != 128) return RF_ERR_BLOCK;
+    if (!valid_block(block)) return RF_ERR_BLOCK;
     if (cls < RF_SPATIAL || cls > RF_LIST_TEMPORAL_POSITION_MAJOR) return RF_ERR_PARAM;
     HostPlan hp;
     build_plan(g, block, &hp);

@@ -44,8 +44,8 @@ struct DirectTile {
     static constexpr int K_BYTES = kTileK * ROW, V_BYTES = kTileK * ROW;
     static constexpr int SEGS = kTileK * CH / 64;  // 1 KiB segments per tile
     static constexpr int V_READS_PER_FRAG = 2;
-    static constexpr int PER_WAVE = SEGS / NW;     // load instructions per tensor per thread
-    static_assert(SEGS % NW == 0, "segments must divide evenly among the wavefronts");
+    static constexpr int PER_WAVE = (SEGS + NW - 1) / NW;  // load instructions per tensor per thread (at most)
+    static constexpr bool EVEN = SEGS % NW == 0;           // else the last round is taken by the first wavefronts only
 
     static __device__ __forceinline__ int k_slot(int row, int chunk) {
         if (D == 128) return chunk ^ (row & 15);
@@ -98,7 +98,7 @@ struct DirectTile {
         k_rot = hf + ((krow >> 2) & 3);
 #pragma unroll
         for (int j = 0; j < PER_WAVE; ++j) {
-            const int slot = (j * NW + wave) * 64 + lane, row = slot / CH, pos = slot % CH;
+            const int slot = min((j * NW + wave) * 64 + lane, kTileK * CH - 1), row = slot / CH, pos = slot % CH;
             if (j < K_VARIANTS) k_lane_off[j] = row * ROW + 16 * k_chunk(row, pos) - j * STEP;
             if (j < V_VARIANTS) v_lane_off[j] = row * ROW + 16 * v_slot(row, pos) - j * STEP;
         }
@@ -117,6 +117,7 @@ struct DirectTile {
 #pragma unroll
         for (int j = 0; j < PER_WAVE; ++j) {
             const int seg = j * NW + wave;
+            if (!EVEN && seg >= SEGS) break;
             const int slot = seg * 64 + lane, row = slot / CH, pos = slot % CH;
             const uint32_t row_off = static_cast<uint32_t>(tok(row)) * ROW;
             dma16(kh, row_off + 16u * k_chunk(row, pos), lds_offset(kl) + seg * 1024);
@@ -129,6 +130,7 @@ struct DirectTile {
 #pragma unroll
         for (int j = 0; j < PER_WAVE; ++j) {
             const int seg = j * NW + wave;
+            if (!EVEN && seg >= SEGS) break;
             dma16(kh + j * STEP, k_lane_off[j % K_VARIANTS], lds_offset(kl) + seg * 1024);
             dma16(vh + j * STEP, v_lane_off[j % V_VARIANTS], lds_offset(vl) + seg * 1024);
         }
@@ -458,7 +460,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
 
 // Wavefronts per SIMD the register allocation is held to: three for head_dim 64 with 128-row
 // blocks (measured best; its accumulators are half the size), two otherwise.
-constexpr int attn_waves_per_simd(int D, int NW) { return (D == 64 && NW == 4) ? 3 : 2; }
+constexpr int attn_waves_per_simd(int D, int NW) { return (D == 64 && NW == 4) ? 3 : 2; }  // NW = 8: one workgroup per CU
 
 template <int D, int NW>
 __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(attn_waves_per_simd(D, NW), attn_waves_per_simd(D, NW)))) attn_kernel(AttnArgs a) {
@@ -584,6 +586,9 @@ int launch_attention(const AttnArgs& a, int D, void* stream) {
     if (D == 96 && nw == 4) return launch_one<96, 4>(a, st);
     if (D == 128 && nw == 2) return launch_one<128, 2>(a, st);
     if (D == 128 && nw == 4) return launch_one<128, 4>(a, st);
+    if (D == 64 && nw == 8) return launch_one<64, 8>(a, st);
+    if (D == 96 && nw == 8) return launch_one<96, 8>(a, st);
+    if (D == 128 && nw == 8) return launch_one<128, 8>(a, st);
     return static_cast<int>(hipErrorInvalidValue);
 }
 

@@ -57,7 +57,7 @@ WORKLOADS = {
     # Open-Sora-Plan-1.2 720p-shaped layer
     "osp720p": Workload("osp720p", 1, 24, 96, 24, 45, 80, 0, 128, 1003),
     # HunyuanVideo 720p-shaped layer, 256 text tokens (headline)
-    "hunyuan720p": Workload("hunyuan720p", 1, 24, 128, 33, 45, 80, 256, 128, 1004),
+    "hunyuan720p": Workload("hunyuan720p", 1, 24, 128, 33, 45, 80, 256, 256, 1004),
     # planted-structure ARM validation
     "planted": Workload("planted", 2, 16, 128, 16, 32, 32, 0, 128, 1005,
                         planted=(SPATIAL, TEMPORAL, TEXTURAL)),

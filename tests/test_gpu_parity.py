@@ -63,7 +63,7 @@ SMALL = ["tiny", "ragged64", "ragged96", "ragged128"]
 
 
 @pytest.mark.parametrize("name", SMALL)
-@pytest.mark.parametrize("block", [64, 128])
+@pytest.mark.parametrize("block", [64, 128, 256])
 @pytest.mark.parametrize("scale", [1.0, 12.0])
 def test_small_shapes_every_class_every_row(name, block, scale):
     w = inp.WORKLOADS[name]
@@ -101,7 +101,7 @@ def test_parameter_corners(bs, bt, tau):
     _, ol = lay(w)
     Q, K, V = inp.full_qkv(w, DEV, 6.0)
     classes = inp.round_robin_classes(w).flatten().tolist()
-    for block, packed in ((64, False), (128, False), (128, True)):
+    for block, packed in ((64, False), (128, False), (128, True), (256, True)):
         O = run_attention(w, Q, K, V, classes, block, rp, packed)
         for b in range(w.B):
             for h in range(w.nH):
@@ -309,6 +309,8 @@ def test_hunyuan720p_headline_layer():
     sampled_parity(w, O, classes, [(0, 0), (0, 8), (0, 16)], 20, tag="thirds")
     O = run_attention(w, Q, K, V, classes, w.block, packed=True)
     sampled_parity(w, O, classes, [(0, 9), (0, 15), (0, 17)], 20, tag="thirds, packed")
+    O = run_attention(w, Q, K, V, classes, 128, packed=True)
+    sampled_parity(w, O, classes, [(0, 1), (0, 10), (0, 20)], 20, tag="thirds, packed, block 128")
     O = run_attention(w, Q, K, V, hc.flatten().tolist(), w.block, packed=True)  # as bench.py runs it
     sampled_parity(w, O, hc.flatten().tolist(), [(0, 5)], 12, tag="arm-chosen, packed")
     O = run_attention(w, Q, K, V, hc.flatten().tolist(), w.block)

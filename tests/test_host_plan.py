@@ -46,7 +46,7 @@ def brute_blocks(M, block):
 
 @pytest.mark.parametrize("lay", LAYOUTS)
 @pytest.mark.parametrize("par", PARAMS)
-@pytest.mark.parametrize("block", [64, 128])
+@pytest.mark.parametrize("block", [64, 128, 256])
 def test_block_lists_match_brute_force(lay, par, block):
     L, P = orc.Layout(*lay), orc.Params(par[0], par[1], par[2])
     rl, rp = rf.rf_layout(*lay), rf.rf_params(par[0], par[1], par[2], 0)
@@ -67,7 +67,7 @@ def test_block_lists_match_brute_force(lay, par, block):
 
 @pytest.mark.parametrize("lay", LAYOUTS)
 @pytest.mark.parametrize("par", PARAMS)
-@pytest.mark.parametrize("block", [64, 128])
+@pytest.mark.parametrize("block", [64, 128, 256])
 def test_position_major_temporal_lists(lay, par, block):
     """The list a Temporal head walks over the position-major copy: the oracle's mask, rows and
     columns permuted into that order, scanned by brute force."""
@@ -94,7 +94,7 @@ def test_position_major_temporal_lists(lay, par, block):
 
 @pytest.mark.parametrize("lay", LAYOUTS)
 @pytest.mark.parametrize("tau", [1, 2, 3])
-@pytest.mark.parametrize("block", [64, 128])
+@pytest.mark.parametrize("block", [64, 128, 256])
 def test_textural_lists(lay, tau, block):
     """Video-only query blocks walk the compacted key sequence; blocks holding text rows walk token space."""
     L, P = orc.Layout(*lay), orc.Params(0.25, 0.25, tau)
@@ -118,7 +118,7 @@ def test_textural_lists(lay, tau, block):
 
 
 @pytest.mark.parametrize("lay", LAYOUTS + [(33, 45, 80, 256), (13, 30, 45, 226)])
-@pytest.mark.parametrize("block", [64, 128])
+@pytest.mark.parametrize("block", [64, 128, 256])
 def test_query_block_order_is_a_permutation(lay, block):
     rl = rf.rf_layout(*lay)
     nqb = -(-(lay[0] * lay[1] * lay[2] + lay[3]) // block)
@@ -182,7 +182,7 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     assert attn(par=rf.rf_params(1.5, 0.25, 2, 0)) == -4 and attn(par=rf.rf_params(0.25, -0.1, 2, 0)) == -4
     assert attn(par=rf.rf_params(0.25, 0.25, 2, 0, 2)) == -4  # unknown flag
     assert attn(par=rf.rf_params(0.25, 0.25, 0, 0)) == -4 and attn(par=rf.rf_params(float("nan"), 0.25, 2, 0)) == -4
-    assert attn(block=32) == -5 and attn(block=256) == -5
+    assert attn(block=32) == -5 and attn(block=512) == -5 and attn(block=0) == -5
     need = rf.rf_attention_workspace_bytes(1, 2, 64, L)
     assert need == 2 * 2 * 256 * 64 * 2  # a copy of K and of V: 2 heads x 256 tokens x 64 channels, bf16
     assert attn(ws=C.c_void_p(256), wsb=need - 1) == -6 and attn(ws=C.c_void_p(264), wsb=need) == -6
