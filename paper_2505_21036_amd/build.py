@@ -18,12 +18,26 @@ def hipcc():
     raise RuntimeError("hipcc not found")
 
 
+def compile_flags(extra_flags=()):
+    # -Wno-inline-asm: the tile loads of rf_attn.hip set M0 in inline assembly and say so in their
+    # clobber list, which clang flags because M0 is a reserved register; tests/test_build_checks.py
+    # verifies on the generated assembly that nothing else in that file uses M0.
+    return ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"),
+            "-I", CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
+            "-Wno-unused-command-line-argument", "-Wno-inline-asm", "-DRF_SCHED_QK=4",
+            "-DRF_SCHED_PV=3"] + list(extra_flags)
+
+
+def device_assembly(source, extra_flags=()):
+    """gfx950 assembly text of one HIP source, compiled with the library's flags."""
+    cmd = [hipcc()] + compile_flags(extra_flags) + ["--cuda-device-only", "-S", os.path.join(CSRC, source), "-o", "-"]
+    return subprocess.run(cmd, check=True, stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True).stdout
+
+
 def build_library(verbose=False, extra_flags=(), out=LIB):
     """Compile every source for gfx950 and link the shared library. Always rebuilds."""
     objs = []
-    flags = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"),
-             "-I", CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
-             "-Wno-unused-command-line-argument", "-DRF_SCHED_QK=4", "-DRF_SCHED_PV=3"] + list(extra_flags)
+    flags = compile_flags(extra_flags)
     procs = []
     for s in SOURCES:
         obj = os.path.join(CSRC, os.path.splitext(s)[0] + ".o")

@@ -19,6 +19,12 @@ enum : int {
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
+// K/V tiles kept in flight ahead of the one being consumed.  Two (with a third buffer) measured no
+// faster than one at any shape: the loads are not what the wavefronts wait for.
+#ifndef RF_TILES_AHEAD
+#define RF_TILES_AHEAD 1
+#endif
+
 // A 64-key tile of K and of V in LDS, filled by global_load_lds (global -> LDS without staging
 // registers) and read back as MFMA operands.
 //
@@ -67,11 +73,19 @@ struct DirectTile {
     static __device__ __forceinline__ uint32_t lds_offset(const unsigned char* p) {
         return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const unsigned char*)p));
     }
-    // One 16-byte-per-lane load from  base + lane offset  into LDS at  lds_addr + 16*lane; completion
-    // is awaited in commit().
+    // One 16-byte-per-lane load from  base + lane offset  into LDS at  lds_addr + 16*lane (lds_addr
+    // wavefront-uniform, handed over in M0); completion is awaited in wait_landed().
+    //
+    // Written as inline assembly rather than with the compiler's builtin on purpose: while a builtin
+    // LDS load is in flight the compiler's wait-count insertion treats it as a pending access to both
+    // memories and degrades every LDS wait in the loop to "all outstanding" (lgkmcnt(0)), and it puts
+    // a full vmcnt(0) in front of the transposing LDS reads, which rules out keeping a second tile in
+    // flight.  Here the waits are explicit instead.  M0 is otherwise unused by the generated code of
+    // this file (a host-side test inspects the assembly for that); the wait state the hardware needs
+    // between the write of M0 and the load is the s_nop.
     static __device__ __forceinline__ void dma16(const unsigned char* base, uint32_t lane_off, uint32_t lds_addr) {
-        __builtin_amdgcn_global_load_lds(base + lane_off, (__attribute__((address_space(3))) void*)(uintptr_t)lds_addr, 16,
-                                         0, 0);
+        const unsigned char* p = base + lane_off;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(p) : "memory", "m0");
     }
 
     int wave, lane;
@@ -135,8 +149,15 @@ struct DirectTile {
             dma16(vh + j * STEP, v_lane_off[j % V_VARIANTS], lds_offset(vl) + seg * 1024);
         }
     }
-    // the tile is in LDS once this thread's loads have landed (the barrier that follows publishes it)
-    __device__ __forceinline__ void commit(unsigned char*, unsigned char*) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+    // Loads land in issue order.  A tile is in LDS once all but the loads issued after its own have
+    // landed (the barrier that follows publishes it): LATER = how many whole tiles were issued after
+    // it.  Every wavefront issues at least MIN_LOADS_PER_TILE loads per tile.
+    static constexpr int MIN_LOADS_PER_TILE = 2 * (SEGS / NW);
+    template <int LATER>
+    static __device__ __forceinline__ void wait_landed() {
+        static_assert(LATER * MIN_LOADS_PER_TILE < 64, "vmcnt is a 6-bit counter");
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LATER * MIN_LOADS_PER_TILE) : "memory");
+    }
 
     // A operand of S^T = K Q^T: keys 32*kb2 .. +31 (permuted per lane), channels 16*c + 8*hf .. +7
     __device__ __forceinline__ bf16x8 k_frag(const unsigned char* kl, int kb2, int c) const {
@@ -149,12 +170,21 @@ struct DirectTile {
         }
         return as_bf16x8(*reinterpret_cast<const u32x4*>(kl + off + kb2 * 32 * ROW));
     }
+    // LDS address of this lane's V operand for u = 0 in tile `vl`, per channel block.  Kept opaque so
+    // that the 32 reads of a tile are this address plus an immediate, not 32 separate address registers.
+    __device__ __forceinline__ void v_addresses(const unsigned char* vl, uint32_t (&va)[D / 32]) const {
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) {
+            va[db] = lds_offset(vl) + v_base[db];
+            asm volatile("" : "+v"(va[db]));
+        }
+    }
     // A operand of O^T = V^T P^T: channels 32*db + lane%32, keys 16*u + 8*hf .. +7
-    __device__ __forceinline__ bf16x8 v_frag(const unsigned char* vl, int db, int u) const {
+    static __device__ __forceinline__ bf16x8 v_frag(uint32_t va, int u) {
         typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-        const unsigned char* p = vl + v_base[db] + 16 * u * ROW;
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * ROW));
+        const uint32_t p = va + 16 * u * ROW;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(p));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(p + 4 * ROW));
         typedef short s16x8 __attribute__((ext_vector_type(8)));
         const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         return __builtin_bit_cast(bf16x8, v);
@@ -169,10 +199,14 @@ struct TileFor {
 template <int D, int NW>
 struct AttnSmem {
     using ST = typename TileFor<D, NW>::type;
+    // K/V tiles resident at a time: the one being consumed plus AHEAD on their way
+    static constexpr int AHEAD = RF_TILES_AHEAD;
+    static constexpr int DEPTH = AHEAD + 1;
+    static constexpr int SIDE_SLOTS = DEPTH + 1;  // side data runs one tile further ahead than K/V
     static constexpr int K_OFF = 0;
-    static constexpr int V_OFF = 2 * ST::K_BYTES;
-    static constexpr int SIDE_OFF = V_OFF + 2 * ST::V_BYTES;  // ring of 3 x 64 ints: key indices or key attributes
-    static constexpr int BYTES = SIDE_OFF + 3 * kTileK * 4;
+    static constexpr int V_OFF = DEPTH * ST::K_BYTES;
+    static constexpr int SIDE_OFF = V_OFF + DEPTH * ST::V_BYTES;  // ring of 64-int slots: key indices or key attributes
+    static constexpr int BYTES = SIDE_OFF + SIDE_SLOTS * kTileK * 4;
 };
 
 struct QueryBlock {
@@ -195,6 +229,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
     constexpr int BQ = 32 * NW;
     using ST = typename TileFor<D, NW>::type;
     using SM = AttnSmem<D, NW>;
+    constexpr int DEPTH = SM::DEPTH;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, m = lane & 31;
     const int N = pl.N, Nv = pl.Nv, keyN = qk.keyN, ntiles = qk.ntiles;
     // per-key side data staged through LDS two tiles ahead: the token index of each key of the
@@ -263,14 +298,14 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
     };
     auto stash_side = [&](int t, int entry) {
         if (!wants_side(entry)) return;
-        if (tid < kTileK) side[(t % 3) * kTileK + tid] = side_reg;
+        if (tid < kTileK) side[(t % SM::SIDE_SLOTS) * kTileK + tid] = side_reg;
     };
-    auto k_lds = [&](int t) { return smem + SM::K_OFF + (t & 1) * ST::K_BYTES; };
-    auto v_lds = [&](int t) { return smem + SM::V_OFF + (t & 1) * ST::V_BYTES; };
+    auto k_lds = [&](int t) { return smem + SM::K_OFF + (t % DEPTH) * ST::K_BYTES; };
+    auto v_lds = [&](int t) { return smem + SM::V_OFF + (t % DEPTH) * ST::V_BYTES; };
     auto fetch_tile = [&](int t, int entry) {
         const int k0 = (entry & kTileIndexMask) * kTileK;
         if (MODE == MODE_COMPACT) {
-            const int* idx = side + (t % 3) * kTileK;
+            const int* idx = side + (t % SM::SIDE_SLOTS) * kTileK;
             st.issue(Kh, Vh, k_lds(t), v_lds(t), [&](int row) { return idx[row]; });
         } else if (k0 + kTileK <= keyN) {
             // full tile: rows are consecutive tokens, everything but the tile origin is loop invariant
@@ -280,7 +315,6 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
             st.issue(Kh, Vh, k_lds(t), v_lds(t), [&](int row) { return min(k0 + row, keyN - 1); });
         }
     };
-    auto stash_tile = [&](int t) { st.commit(k_lds(t), v_lds(t)); };
 
     // S^T of tile t (64 keys x this lane's query), predicate applied where the tile is partial
     auto scores = [&](int t, int entry, f32x16 (&s)[2]) {
@@ -305,7 +339,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
 #endif
         if (entry & RF_PLAN_PARTIAL) {
             const int k0 = (entry & kTileIndexMask) * kTileK;
-            const int* al = side + (t % 3) * kTileK;
+            const int* al = side + (t % SM::SIDE_SLOTS) * kTileK;
             if (MODE == MODE_LISTED && !(entry & kTileBoundary)) {
                 // all 64 keys are video tokens: only the pattern's band decides
 #pragma unroll
@@ -346,29 +380,59 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
         return sum;
     };
 
-    // software pipeline: side data runs two tiles ahead of the compute, K/V one tile ahead
-    int e_cur = 0, e_nxt = 0, e_nx2 = 0;
-    if (ntiles > 0) {
-        e_cur = entry_of(0);
-        if (ntiles > 1) e_nxt = entry_of(1);
-        load_side(e_cur);
-        stash_side(0, e_cur);
-        if (ntiles > 1) {
-            load_side(e_nxt);
-            stash_side(1, e_nxt);
+    // O^T += V^T P^T for tile t, P (bf16) in pf
+    bf16x8 pf[4];
+    auto accumulate = [&](int t) {
+        uint32_t va[D / 32];
+        st.v_addresses(v_lds(t), va);
+        // consecutive MFMAs go to different accumulators (channel blocks): no back-to-back dependence
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ST::v_frag(va[db], u), pf[u], oacc[db], 0, 0, 0);
+#ifdef RF_SCHED_PV
+        {
+            constexpr int PER = ST::V_READS_PER_FRAG, TOTAL = 4 * (D / 32);
+            __builtin_amdgcn_sched_group_barrier(0x100, RF_SCHED_PV * PER, 1);
+#pragma unroll
+            for (int i = 0; i < TOTAL - RF_SCHED_PV; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+                __builtin_amdgcn_sched_group_barrier(0x100, PER, 1);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, RF_SCHED_PV, 1);
         }
-    }
+#endif
+    };
+    // Software pipeline.  While tile t is consumed, the loads of tiles t+1 .. t+AHEAD are in flight
+    // or landed, and the side data of tile t+DEPTH is on its way to its ring slot (one tile further,
+    // because the loads of a compacted tile take their row indices from it).  e[i] = entry of tile t+i.
+    constexpr int AHEAD = SM::AHEAD;
+    int e[DEPTH + 1] = {};
+#pragma unroll
+    for (int i = 0; i < DEPTH; ++i)
+        if (i < ntiles) {
+            e[i] = entry_of(i);
+            load_side(e[i]);
+            stash_side(i, e[i]);
+        }
     __syncthreads();
-    if (ntiles > 0) {
-        fetch_tile(0, e_cur);
-        stash_tile(0);
-    }
+#pragma unroll
+    for (int i = 0; i < AHEAD; ++i)
+        if (i < ntiles) fetch_tile(i, e[i]);
+    ST::template wait_landed<0>();
     __syncthreads();
+    // The compiler cannot see the tile loads above, so its own wait for the Q loads, if left inside
+    // the loop, would count them out too and wait for the tiles in flight; make it wait here.
+#pragma unroll
+    for (int cc = 0; cc < D / 16; ++cc) asm volatile("" ::"v"(__builtin_bit_cast(u32x4, qf[cc])));
 
     for (int t = 0; t < ntiles; ++t) {
-        if (t + 2 < ntiles) e_nx2 = entry_of(t + 2);
-        if (t + 1 < ntiles) fetch_tile(t + 1, e_nxt);
-        if (t + 2 < ntiles) load_side(e_nx2);
+        // the buffer of tile t+AHEAD held tile t+AHEAD-DEPTH, which every wavefront left before the last barrier
+        if (t + DEPTH < ntiles) e[DEPTH] = entry_of(t + DEPTH);
+        if (t + AHEAD < ntiles) fetch_tile(t + AHEAD, e[AHEAD]);
+        if (t + DEPTH < ntiles) load_side(e[DEPTH]);
+        const int e_cur = e[0];
 
         // Online softmax (Eq. 1) in base 2 with 1/sqrt(D) folded into c.  The reference subtracted in
         // the exponent is moved, and the accumulators rescaled, only when a row outgrows it by more
@@ -400,7 +464,6 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
         const float psum = exponentiate(s);
         l_run += psum;
 
-        bf16x8 pf[4];
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
@@ -412,34 +475,16 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
                 w.w = pack_bf16(s[kb2][8 * u2 + 6], s[kb2][8 * u2 + 7]);
                 pf[2 * kb2 + u2] = as_bf16x8(w);
             }
+        accumulate(t);
 
-        const unsigned char* vl = v_lds(t);
-        // consecutive MFMAs go to different accumulators (channel blocks): no back-to-back dependence
+        // tile t+1 must be in LDS at the barrier; the loads of the tiles after it may stay in flight
+        if (AHEAD > 1 && t + AHEAD < ntiles) ST::template wait_landed<AHEAD - 1>();
+        else ST::template wait_landed<0>();
+        if (t + DEPTH < ntiles) stash_side(t + DEPTH, e[DEPTH]);
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-            for (int db = 0; db < D / 32; ++db)
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st.v_frag(vl, db, u), pf[u], oacc[db], 0, 0, 0);
-#ifdef RF_SCHED_PV
-        {
-            constexpr int PER = ST::V_READS_PER_FRAG, TOTAL = 4 * (D / 32);
-            __builtin_amdgcn_sched_group_barrier(0x100, RF_SCHED_PV * PER, 1);
-#pragma unroll
-            for (int i = 0; i < TOTAL - RF_SCHED_PV; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-                __builtin_amdgcn_sched_group_barrier(0x100, PER, 1);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, RF_SCHED_PV, 1);
-        }
-#endif
-
-        if (t + 1 < ntiles) stash_tile(t + 1);
-        if (t + 2 < ntiles) stash_side(t + 2, e_nx2);
-        e_cur = e_nxt;
-        e_nxt = e_nx2;
+        for (int i = 0; i < DEPTH; ++i) e[i] = e[i + 1];
         __syncthreads();
     }
-
     // Eq. 2: divide by the softmax denominator and store.  Lane (hf, m) owns query m and, per
     // 32-channel block, channels 8*(r/4) + 4*hf + r%4.
     const float l_tot = l_run + other_half(l_run);
