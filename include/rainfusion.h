@@ -9,8 +9,8 @@
  *     [B, nH, N, D] (batch, head, token, channel).  The library neither frees nor
  *     keeps them.  D is 64, 96 or 128.
  *   - Token order (Sec. 3.1): T frames of H*W tokens each, frame-major, row-major
- *     inside a frame; text_len text tokens follow the video tokens.
- *     N = T*H*W + text_len.
+ *     inside a frame; text_len text tokens follow the video tokens, or precede
+ *     them under RF_FLAG_TEXT_FIRST.  N = T*H*W + text_len.
  *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) and never synchronise it, except that the first call for a new
  *     (layout, params, block) builds and uploads its block lists synchronously.
@@ -40,8 +40,7 @@ typedef struct {
  *                 in every frame.  Both products are formed in double precision.
  *   tex_stride  : tau of Eq. 4; a key at row y, column x of any frame survives iff (y - x) mod tau == 0.
  *   sample_interval : omega of Sec. 3.3 (global sampling keeps tokens 0, omega, 2*omega, ...); 0 means T.
- *   flags       : 0, or RF_FLAG_TWO_HEAD.  (The paper's "first 10 % of the timesteps dense" needs no flag:
- *                 pass RF_DENSE for every head on those steps.)
+ *   flags       : 0 or an OR of RF_FLAG_* below.
  * Text tokens attend and are attended densely under every pattern and are never sampled by the ARM. */
 typedef struct {
     float bw_spatial, bw_temporal;
@@ -53,6 +52,14 @@ typedef struct {
 /* Two-head ablation (Sec. 4.2, Tab. 2 rows without "Te"): the ARM sends a head that matches neither
  * the Temporal nor the Spatial mask to RF_DENSE instead of RF_TEXTURAL. */
 #define RF_FLAG_TWO_HEAD 1
+/* The text tokens are the FIRST text_len rows of every tensor and the video tokens follow them (the
+ * order of models that prepend the prompt).  The paper does not place the text tokens; the masks
+ * are defined on the video tokens' (frame, row, column), so only where those sit changes. */
+#define RF_FLAG_TEXT_FIRST 2
+/* rf_sparse_attention treats every head as RF_DENSE and does not read head_class (which may then be
+ * NULL): the "first 10 % of the timesteps dense" policy of Sec. 4.1 without touching the class
+ * buffer.  Ignored by the ARM. */
+#define RF_FLAG_FORCE_DENSE 4
 
 #define RF_MAX_BANDWIDTHS 4 /* candidate bandwidths of the per-head bandwidth variant */
 
@@ -121,7 +128,7 @@ int rf_arm_classify_plus(const void *Q, const void *K, int B, int nH, int D, con
  * Q, K, V     : device, bf16 [B, nH, N, D].
  * head_class  : device, int32 [B*nH], values of rf_head_class; read on the device, so the
  *               output of rf_arm_classify can be passed on without a host round trip.
- *               Values outside 0..3 are treated as RF_DENSE.
+ *               Values outside 0..3 are treated as RF_DENSE.  May be NULL under RF_FLAG_FORCE_DENSE.
  * O           : device, bf16 [B, nH, N, D], written.
  * workspace   : optional device scratch of at least rf_attention_workspace_bytes() bytes, 16-byte
  *               aligned.  If given, K and V of the heads that profit are first copied into it in a
@@ -165,6 +172,8 @@ size_t rf_attention_workspace_bytes(int B, int nH, int D, const rf_layout *layou
  *             workspace is given: query blocks and key tiles are then runs of the position-major
  *             order (see rf_plan_position_major).
  *   needed  : host, receives the number of entries.
+ * Under RF_FLAG_TEXT_FIRST rows are counted in the order the kernel walks: video tokens first
+ * (row r < T*H*W is token text_len + r), then the text tokens.
  * Returns RF_ERR_WORKSPACE if cap < *needed (nothing but *needed and row_ptr is written then).
  */
 #define RF_PLAN_PARTIAL 0x40000000
@@ -182,9 +191,10 @@ int rf_plan_host(const rf_layout *layout, const rf_params *params, int block, in
 int rf_plan_order(const rf_layout *layout, const rf_params *params, int block, int cls, int32_t *order);
 
 /* Position-major order of the tokens: token_of (host, int32 [N]) receives, for every row of that
- * order, the token it holds: video token (frame f, in-frame position p) is row p*T + f, text
- * tokens keep their place after the video tokens. */
-int rf_plan_position_major(const rf_layout *layout, int32_t *token_of);
+ * order, the token (row of the caller's tensors) it holds: video token (frame f, in-frame position
+ * p) is row p*T + f, the text tokens are the last text_len rows.  Only RF_FLAG_TEXT_FIRST of
+ * `params` (may be NULL) matters. */
+int rf_plan_position_major(const rf_layout *layout, const rf_params *params, int32_t *token_of);
 
 /* Drop every cached block list and free its device memory (synchronises the device). */
 int rf_plan_clear(void);

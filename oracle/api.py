@@ -25,7 +25,8 @@ class _CLayout(C.Structure):
 
 class _CParams(C.Structure):
     _fields_ = [("bw_spatial", C.c_double), ("bw_temporal", C.c_double),
-                ("tex_stride", C.c_int32), ("sample_interval", C.c_int32), ("two_head", C.c_int32)]
+                ("tex_stride", C.c_int32), ("sample_interval", C.c_int32), ("two_head", C.c_int32),
+                ("text_first", C.c_int32)]
 
 
 @dataclass(frozen=True)
@@ -49,11 +50,12 @@ class Params:
     tex_stride: int = 2
     sample_interval: int = 0
     two_head: bool = False
+    text_first: bool = False  # the text tokens come before the video tokens instead of after
 
     def c(self):
         # the library takes the bandwidths as float32; promote those exact values
         return _CParams(float(np.float32(self.bw_spatial)), float(np.float32(self.bw_temporal)),
-                        self.tex_stride, self.sample_interval, int(self.two_head))
+                        self.tex_stride, self.sample_interval, int(self.two_head), int(self.text_first))
 
 
 def build(force=False):

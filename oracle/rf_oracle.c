@@ -9,7 +9,9 @@
  *
  * What it follows (RainFusion, arxiv 2505.21036):
  *   - token layout, Sec. 3.1: the sequence is T frame sub-sequences of H*W
- *     tokens each; optional text tokens are appended after the video tokens;
+ *     tokens each; optional text tokens are appended after the video tokens
+ *     (or, with text_first set, placed in front of them: the paper does not say
+ *     where a model's prompt tokens sit, and models differ);
  *   - masked softmax attention, Eq. 1-2;
  *   - the three pattern masks of Sec. 3.2 (Spatial Eq. 3, Temporal, Textural
  *     Eq. 4-5) written as one token-level predicate rfo_keep();
@@ -51,6 +53,7 @@ typedef struct {
     int32_t sample_interval;        /* omega of Sec. 3.3; <= 0 means T */
     int32_t two_head;               /* ablation of Sec. 4.2 / Tab. 2: only Spatial and Temporal heads are sparse,
                                        every other head is computed densely */
+    int32_t text_first;             /* the text tokens are tokens 0 .. text_len-1 and the video follows */
 } rfo_params;
 
 static int64_t n_video(const rfo_layout *L) { return (int64_t)L->T * L->H * L->W; }
@@ -65,12 +68,21 @@ int64_t rfo_radius(double bw, int64_t n)
     return (int64_t)r;
 }
 
+/* Index of token n among the video tokens (frame-major order of Sec. 3.1), or -1 for a text token. */
+static int64_t video_index(int64_t n, const rfo_layout *L, const rfo_params *P)
+{
+    if (P->text_first) return n < L->text_len ? -1 : n - L->text_len;
+    return n < n_video(L) ? n : -1;
+}
+
 /* Sec. 3.2 as one predicate: does query token i see key token j under pattern cls? */
 int rfo_keep(int cls, int64_t i, int64_t j, const rfo_layout *L, const rfo_params *P)
 {
-    const int64_t HW = (int64_t)L->H * L->W, Nv = n_video(L);
+    const int64_t HW = (int64_t)L->H * L->W;
     if (cls == RFO_DENSE) return 1;
-    if (i >= Nv || j >= Nv) return 1; /* text rows and text columns stay dense */
+    i = video_index(i, L, P);
+    j = video_index(j, L, P);
+    if (i < 0 || j < 0) return 1; /* text rows and text columns stay dense */
     const int64_t fi = i / HW, pi = i % HW, fj = j / HW, pj = j % HW;
     if (cls == RFO_SPATIAL) {
         int64_t r = rfo_radius(P->bw_spatial, L->T);
@@ -203,9 +215,10 @@ int64_t rfo_sample_count(const rfo_layout *L, const rfo_params *P, int global)
 }
 int64_t rfo_sample_token(const rfo_layout *L, const rfo_params *P, int global, int64_t a)
 {
-    if (!global) return a;
+    const int64_t first_video = P->text_first ? L->text_len : 0; /* samples are video tokens */
+    if (!global) return first_video + a;
     const int64_t w = P->sample_interval > 0 ? P->sample_interval : L->T;
-    return a * w;
+    return first_video + a * w;
 }
 
 /*

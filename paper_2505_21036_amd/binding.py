@@ -13,6 +13,8 @@ import numpy as np
 RF_SPATIAL, RF_TEMPORAL, RF_TEXTURAL, RF_DENSE = 0, 1, 2, 3
 RF_SAMPLE_FIRST_FRAME, RF_SAMPLE_EQUAL_INTERVAL = 0, 1
 RF_FLAG_TWO_HEAD = 1
+RF_FLAG_TEXT_FIRST = 2
+RF_FLAG_FORCE_DENSE = 4
 RF_PLAN_PARTIAL = 0x40000000
 RF_KEY_TILE = 64
 RF_LIST_TEMPORAL_POSITION_MAJOR = 4
@@ -81,7 +83,7 @@ def load_library():
     lib.rf_plan_order.restype = C.c_int
     lib.rf_plan_order.argtypes = [PL, PP, C.c_int, C.c_int, vp]
     lib.rf_plan_position_major.restype = C.c_int
-    lib.rf_plan_position_major.argtypes = [PL, vp]
+    lib.rf_plan_position_major.argtypes = [PL, PP, vp]
     lib.rf_plan_clear.restype = C.c_int
     lib.rf_plan_clear.argtypes = []
     _lib = lib
@@ -198,7 +200,8 @@ def rf_attention_workspace_bytes(B, nH, D, layout, params=None):
 
 
 def rf_sparse_attention(Q, K, V, head_class, layout, params=None, block=128, out=None, workspace=None):
-    """Sparse attention forward (Eq. 1-5). head_class: int32 device tensor [B, nH]. Returns O.
+    """Sparse attention forward (Eq. 1-5). head_class: int32 device tensor [B, nH] (may be None under
+    RF_FLAG_FORCE_DENSE). Returns O.
     workspace: optional uint8 device tensor of rf_attention_workspace_bytes() bytes (packs K_C, V_C)."""
     import torch
     _check_bf16(Q, "Q")
@@ -207,8 +210,8 @@ def rf_sparse_attention(Q, K, V, head_class, layout, params=None, block=128, out
     B, nH, N, D = Q.shape
     if N != layout.T * layout.H * layout.W + layout.text_len:
         raise ValueError("N does not match the layout")
-    if not (head_class.is_cuda and head_class.dtype == torch.int32 and head_class.is_contiguous()
-            and head_class.numel() == B * nH):
+    if head_class is not None and not (head_class.is_cuda and head_class.dtype == torch.int32
+                                       and head_class.is_contiguous() and head_class.numel() == B * nH):
         raise ValueError("head_class must be a contiguous int32 device tensor with B*nH entries")
     if out is None:
         out = torch.empty_like(Q)
@@ -216,7 +219,8 @@ def rf_sparse_attention(Q, K, V, head_class, layout, params=None, block=128, out
         _check_bf16(out, "out", Q.shape)
     ws_ptr, ws_bytes = (None, 0) if workspace is None else (workspace.data_ptr(),
                                                            workspace.numel() * workspace.element_size())
-    st = load_library().rf_sparse_attention(Q.data_ptr(), K.data_ptr(), V.data_ptr(), head_class.data_ptr(), B, nH,
+    hc_ptr = None if head_class is None else head_class.data_ptr()
+    st = load_library().rf_sparse_attention(Q.data_ptr(), K.data_ptr(), V.data_ptr(), hc_ptr, B, nH,
                                             D, C.byref(layout), _pp(params), block, out.data_ptr(), ws_ptr, ws_bytes,
                                             _stream())
     if st != 0:
@@ -252,11 +256,11 @@ def rf_plan_order(layout, params, block, cls):
     return order
 
 
-def rf_plan_position_major(layout):
+def rf_plan_position_major(layout, params=None):
     """token_of[row] for the position-major order of the tokens (int32 [N])."""
     N = layout.T * layout.H * layout.W + layout.text_len
     out = np.full(N, -1, dtype=np.int32)
-    st = load_library().rf_plan_position_major(C.byref(layout), out.ctypes.data)
+    st = load_library().rf_plan_position_major(C.byref(layout), _pp(params), out.ctypes.data)
     if st != 0:
         raise RfError(st, "rf_plan_position_major")
     return out

@@ -97,6 +97,8 @@ int get_attention_plan(const Geometry& g, int block, const DevicePlan** out) {
         d.radius[RF_TEMPORAL] = g.r_temporal;
         d.radius[RF_TEXTURAL] = 0;
         d.radius[kListTemporalPM] = g.r_temporal;
+        d.video_shift = g.video_shift();
+        d.text_shift = g.text_shift();
         d.N = g.N; d.Nv = g.Nv; d.Nc = hp.Nc;
         d.block = block; d.nQB = hp.nQB; d.nKT = hp.nKT; d.nCT = hp.nCT;
         d.first_text_qb = hp.first_text_qb;
@@ -242,6 +244,7 @@ static int arm_classify_impl(const void* Q, const void* K, int B, int nH, int D,
     a.K = static_cast<const uint16_t*>(K);
     a.BH = B * nH;
     a.N = g.N;
+    a.first_video_row = g.video_shift();
     a.scale_log2 = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(D)));
     if (sample_mode == RF_SAMPLE_FIRST_FRAME) a.pass[0] = ArmPass{tb->local_pos, g.HW, 1, {0}};
     else a.pass[0] = ArmPass{tb->global_pos, tb->nG, g.omega, {0}};
@@ -288,7 +291,9 @@ static int sparse_attention_impl(const void* Q, const void* K, const void* V, co
                                  const int32_t* head_bw, const float* bandwidths, int n_bw, int B, int nH, int D,
                                  const rf_layout* layout, const rf_params* params, int block, void* O, void* workspace,
                                  size_t workspace_bytes, void* stream) {
-    if (!Q || !K || !V || !O || !head_class || !layout) return RF_ERR_NULL;
+    if (!Q || !K || !V || !O || !layout) return RF_ERR_NULL;
+    const bool force_dense = params && (params->flags & RF_FLAG_FORCE_DENSE);
+    if (!head_class && !force_dense) return RF_ERR_NULL;
     Geometry g;
     int st = resolve_geometry(layout, params, &g);
     if (st != RF_OK) return st;
@@ -315,11 +320,11 @@ static int sparse_attention_impl(const void* Q, const void* K, const void* V, co
     a.K = static_cast<const uint16_t*>(K);
     a.V = static_cast<const uint16_t*>(V);
     a.O = static_cast<uint16_t*>(O);
-    a.head_class = head_class;
+    a.head_class = force_dense ? nullptr : head_class;
     a.head_bw = bandwidths ? head_bw : nullptr;
     a.BH = B * nH;
     a.scale_log2 = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(D)));
-    if (workspace) {
+    if (workspace && !force_dense) {
         a.packed_k = static_cast<uint16_t*>(workspace);
         a.packed_v = a.packed_k + static_cast<size_t>(B) * nH * g.N * D;
         if (launch_pack_textural(a, D, stream) != 0) return RF_ERR_HIP;
@@ -380,13 +385,13 @@ int rf_plan_order(const rf_layout* layout, const rf_params* params, int block, i
     return RF_OK;
 }
 
-int rf_plan_position_major(const rf_layout* layout, int32_t* token_of) {
+int rf_plan_position_major(const rf_layout* layout, const rf_params* params, int32_t* token_of) {
     if (!layout || !token_of) return RF_ERR_NULL;
     Geometry g;
-    const int st = resolve_geometry(layout, nullptr, &g);
+    const int st = resolve_geometry(layout, params, &g);
     if (st != RF_OK) return st;
-    for (int n = 0; n < g.Nv; ++n) token_of[n] = (n % g.T) * g.HW + n / g.T;
-    for (int n = g.Nv; n < g.N; ++n) token_of[n] = n;
+    for (int n = 0; n < g.Nv; ++n) token_of[n] = g.row_of((n % g.T) * g.HW + n / g.T);
+    for (int n = g.Nv; n < g.N; ++n) token_of[n] = g.row_of(n);
     return RF_OK;
 }
 

@@ -29,7 +29,8 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
     if (qb * BQ >= n) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, m = lane & 31;
 
-    const size_t head_off = static_cast<size_t>(bh) * a.N * D;
+    // samples are video tokens; first_video_row is where those start in the tensors
+    const size_t head_off = (static_cast<size_t>(bh) * a.N + a.first_video_row) * D;
     const uint16_t* Qh = a.Q + head_off;
     const uint16_t* Kh = a.K + head_off;
 

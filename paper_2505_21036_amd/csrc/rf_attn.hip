@@ -215,6 +215,9 @@ struct QueryBlock {
     const int32_t* row_token;    // null, or: row of the walked order -> token (queries are gathered, O scattered)
     const unsigned char* kbase;  // K and V rows of the key sequence walked (the head's, or its compacted copy)
     const unsigned char* vbase;
+    // tensor row of walked index n = n + (n < Nv ? video_shift : text_shift); both 0 unless the text
+    // tokens come first in the tensors, and 0 when kbase/vbase are packed copies (already in walked order)
+    int video_shift, text_shift;
     const int32_t* cols;  // MODE_LISTED: this query block's tile entries
     int ntiles;           // key tiles to visit
     int keyN;             // length of the key sequence walked (N, or Nc when compacted)
@@ -244,7 +247,8 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
     // this lane's query
     const int qrow = qk.qb * BQ + wave * 32 + m;  // row of the walked order
     const int qrow_c = min(qrow, N - 1);
-    const int qtok = (MODE == MODE_LISTED && qk.row_token) ? qk.row_token[qrow_c] : qrow_c;
+    const int qtok = (MODE == MODE_LISTED && qk.row_token) ? qk.row_token[qrow_c]
+                                                           : qrow_c + (qrow_c < Nv ? pl.video_shift : pl.text_shift);
     bf16x8 qf[D / 16];
     load_q_frags<D>(Qh, qtok, hf, qf);
     int q_attr = 0, q_rad = 0x3fffffff;  // text queries keep everything
@@ -307,12 +311,16 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
         if (MODE == MODE_COMPACT) {
             const int* idx = side + (t % SM::SIDE_SLOTS) * kTileK;
             st.issue(Kh, Vh, k_lds(t), v_lds(t), [&](int row) { return idx[row]; });
-        } else if (k0 + kTileK <= keyN) {
-            // full tile: rows are consecutive tokens, everything but the tile origin is loop invariant
-            const size_t origin = static_cast<size_t>(k0) * (2 * D);
+        } else if (k0 + kTileK <= keyN && !(qk.text_shift != 0 && k0 < Nv && k0 + kTileK > Nv)) {
+            // full tile of consecutive tensor rows: everything but the tile origin is loop invariant
+            const int r0 = k0 + (k0 < Nv ? qk.video_shift : qk.text_shift);
+            const size_t origin = static_cast<size_t>(r0) * (2 * D);
             st.issue_consecutive(Kh + origin, Vh + origin, k_lds(t), v_lds(t));
         } else {
-            st.issue(Kh, Vh, k_lds(t), v_lds(t), [&](int row) { return min(k0 + row, keyN - 1); });
+            st.issue(Kh, Vh, k_lds(t), v_lds(t), [&](int row) {
+                const int n = min(k0 + row, keyN - 1);
+                return n + (n < Nv ? qk.video_shift : qk.text_shift);
+            });
         }
     };
 
@@ -528,7 +536,7 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
         if (static_cast<unsigned>(which) >= static_cast<unsigned>(a.n_plans)) which = 0;
     }
     const DevicePlan& pl = a.plan[which];
-    int cls = a.head_class[qk.bh];
+    int cls = a.head_class ? a.head_class[qk.bh] : RF_DENSE;
     if (static_cast<unsigned>(cls) > 3u) cls = RF_DENSE;
     qk.cls = cls;
     // a Temporal head walks the position-major copy of its K and V if the caller gave room for one
@@ -538,6 +546,8 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
     qk.cols = nullptr;
     qk.list = cls;
     qk.row_token = nullptr;
+    qk.video_shift = pl.video_shift;
+    qk.text_shift = pl.text_shift;
     const size_t head_bytes = static_cast<size_t>(qk.bh) * pl.N * D * 2;
     qk.kbase = reinterpret_cast<const unsigned char*>(a.K) + head_bytes;
     qk.vbase = reinterpret_cast<const unsigned char*>(a.V) + head_bytes;
@@ -555,6 +565,7 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
             const size_t packed_bytes = head_bytes;
             qk.kbase = reinterpret_cast<const unsigned char*>(a.packed_k) + packed_bytes;
             qk.vbase = reinterpret_cast<const unsigned char*>(a.packed_v) + packed_bytes;
+            qk.video_shift = qk.text_shift = 0;
             attend<D, NW, MODE_ALL>(a, pl, qk, smem);
         } else {
             attend<D, NW, MODE_COMPACT>(a, pl, qk, smem);
@@ -565,6 +576,7 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
             qk.row_token = pl.pm_token;
             qk.kbase = reinterpret_cast<const unsigned char*>(a.packed_k) + head_bytes;
             qk.vbase = reinterpret_cast<const unsigned char*>(a.packed_v) + head_bytes;
+            qk.video_shift = qk.text_shift = 0;
         }
         const int e0 = pl.row_ptr[list][qk.qb];
         qk.ntiles = pl.row_ptr[list][qk.qb + 1] - e0;

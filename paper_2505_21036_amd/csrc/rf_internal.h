@@ -24,6 +24,13 @@ struct Geometry {
     int tau;                    // checkerboard stride (Eq. 4)
     int omega;                  // global sampling interval (Sec. 3.3)
     int two_head;               // ARM fallback class is DENSE instead of TEXTURAL
+    int text_first;             // text tokens are the first rows of the tensors instead of the last
+
+    // Lists, attributes and orders are all built on the WALKED order: video tokens 0 .. Nv-1, then
+    // text.  row_of() gives the tensor row of a walked index (the identity unless text_first).
+    int video_shift() const { return text_first ? text_len : 0; }  // added to a walked video index
+    int text_shift() const { return text_first ? -Nv : 0; }        // added to a walked text index
+    int row_of(int n) const { return n + (n < Nv ? video_shift() : text_shift()); }
 };
 
 // Lists: 0/1/2 = Spatial / Temporal / Textural in token order; 3 = Temporal in POSITION-MAJOR
@@ -46,8 +53,8 @@ struct HostPlan {
     std::vector<int32_t> qorder[kLists];  // order in which a head's query blocks are handed out (a permutation)
     // per row of the list's order: frame index / in-frame index / 0 if kept by Eq. 4 else 1 / in-frame index
     std::vector<int32_t> attr[kLists];
-    std::vector<int32_t> cidx;      // compacted position -> token index (Textural)
-    std::vector<int32_t> pm_token;  // position-major row -> token index
+    std::vector<int32_t> cidx;      // compacted position -> tensor row (Textural)
+    std::vector<int32_t> pm_token;  // position-major row -> tensor row
 };
 
 // Fills g from layout/params (params may be null -> paper defaults). Returns an rf_status.
@@ -68,6 +75,7 @@ struct DevicePlan {
     const int32_t* cidx;
     const int32_t* pm_token;
     int radius[kLists];
+    int video_shift, text_shift;  // tensor row = walked index + (index < Nv ? video_shift : text_shift)
     int N, Nv, Nc;
     int block, nQB, nKT, nCT, first_text_qb;
 };
@@ -78,7 +86,7 @@ struct AttnArgs {
     const uint16_t* K;
     const uint16_t* V;
     uint16_t* O;
-    const int32_t* head_class;
+    const int32_t* head_class;  // null: every head dense
     int BH;            // B * nH
     float scale_log2;  // log2(e) / sqrt(D)
     // optional: packed copies of K and V, [BH][N][D] each: the kept rows of Textural heads (first Nc rows),
@@ -103,6 +111,7 @@ struct ArmArgs {
     const uint16_t* Q;
     const uint16_t* K;
     int BH, N;
+    int first_video_row;  // tensor row of video token 0
     float scale_log2;
     ArmPass pass[2];   // 0: Temporal mask (R_hat), 1: Spatial mask (R_tilde)
     int n_bw;          // candidate bandwidths (1 for plain Alg. 1)

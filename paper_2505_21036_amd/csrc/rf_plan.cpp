@@ -32,7 +32,7 @@ int resolve_geometry(const rf_layout* L, const rf_params* P, Geometry* g) {
     if (!(p->bw_spatial >= 0.f && p->bw_spatial <= 1.f)) return RF_ERR_PARAM;
     if (!(p->bw_temporal >= 0.f && p->bw_temporal <= 1.f)) return RF_ERR_PARAM;
     if (p->tex_stride < 1 || p->sample_interval < 0) return RF_ERR_PARAM;
-    if (p->flags & ~RF_FLAG_TWO_HEAD) return RF_ERR_PARAM;
+    if (p->flags & ~(RF_FLAG_TWO_HEAD | RF_FLAG_TEXT_FIRST | RF_FLAG_FORCE_DENSE)) return RF_ERR_PARAM;
     g->T = L->T; g->H = L->H; g->W = L->W; g->text_len = L->text_len;
     g->HW = static_cast<int>(HW); g->Nv = static_cast<int>(Nv); g->N = static_cast<int>(N);
     g->r_spatial = band_radius(p->bw_spatial, L->T);
@@ -40,6 +40,7 @@ int resolve_geometry(const rf_layout* L, const rf_params* P, Geometry* g) {
     g->tau = p->tex_stride;
     g->omega = p->sample_interval > 0 ? p->sample_interval : L->T;
     g->two_head = (p->flags & RF_FLAG_TWO_HEAD) ? 1 : 0;
+    g->text_first = (p->flags & RF_FLAG_TEXT_FIRST) && L->text_len > 0 ? 1 : 0;
     return RF_OK;
 }
 
@@ -144,19 +145,19 @@ void build_plan(const Geometry& g, int block, HostPlan* plan) {
     P.pm_token.resize(N);
     for (int n = 0; n < Nv; ++n) {  // position-major row n = p*T + f
         const int p = n / g.T, f = n % g.T;
-        P.pm_token[n] = f * HW + p;
+        P.pm_token[n] = g.row_of(f * HW + p);
         P.attr[kListTemporalPM][n] = p;
     }
-    for (int n = Nv; n < N; ++n) P.pm_token[n] = n;
+    for (int n = Nv; n < N; ++n) P.pm_token[n] = g.row_of(n);
     for (int n = 0; n < Nv; ++n) {
         const int f = n / HW, p = n % HW, y = p / g.W, x = p % g.W;
         P.attr[RF_SPATIAL][n] = f;
         P.attr[RF_TEMPORAL][n] = p;
         const bool kept = ((y - x) % g.tau) == 0;
         P.attr[RF_TEXTURAL][n] = kept ? 0 : 1;
-        if (kept) P.cidx.push_back(n);
+        if (kept) P.cidx.push_back(g.row_of(n));
     }
-    for (int n = Nv; n < N; ++n) P.cidx.push_back(n);
+    for (int n = Nv; n < N; ++n) P.cidx.push_back(g.row_of(n));
     P.Nc = static_cast<int>(P.cidx.size());
     P.nCT = (P.Nc + kTileK - 1) / kTileK;
 

@@ -140,6 +140,55 @@ def test_out_of_range_class_runs_dense_and_constant_values_give_ones():
         assert (O.float() - 1).abs().max().item() <= 1e-2
 
 
+# ----------------------------------------------------------------------------- text tokens first, forced dense
+@pytest.mark.parametrize("name", ["ragged64", "ragged96", "ragged128"])
+@pytest.mark.parametrize("block", [64, 128, 256])
+def test_text_first_every_class_every_row(name, block):
+    """The same heads with their text rows moved to the front and RF_FLAG_TEXT_FIRST set, against
+    the oracle's text-first reading; attention for every class, packed or not, and the ARM."""
+    w = inp.WORKLOADS[name]
+    print("case text-first", name, block, flush=True)
+    tl, scale = w.text_len, 6.0
+    rl, ol = lay(w)
+    rp, op = rf.rf_params(0.25, 0.25, 2, 0, rf.RF_FLAG_TEXT_FIRST), orc.Params(text_first=True)
+    Q, K, V = (torch.roll(t, tl, dims=2).contiguous() for t in inp.full_qkv(w, DEV, scale))
+    heads = {(b, h): [np.roll(f32(t), tl, axis=0) for t in inp.head_qkv(w, b, h, scale)]
+             for b in range(w.B) for h in range(w.nH)}
+    for cls, packed in ((rf.RF_SPATIAL, False), (rf.RF_TEMPORAL, False), (rf.RF_TEMPORAL, True),
+                        (rf.RF_TEXTURAL, False), (rf.RF_TEXTURAL, True), (rf.RF_DENSE, False)):
+        O = run_attention(w, Q, K, V, [cls] * (w.B * w.nH), block, rp, packed)
+        for (b, h), (q, k, v) in heads.items():
+            check(O[b, h], orc.attention(q, k, v, cls, ol, op),
+                  "%s text-first blk%d cls%d packed%d head(%d,%d)" % (name, block, cls, packed, b, h))
+    for mode in (rf.RF_SAMPLE_FIRST_FRAME, rf.RF_SAMPLE_EQUAL_INTERVAL):
+        hc, rec = rf.rf_arm_classify(Q, K, rl, rp, mode, 0.5)
+        hc, rec = hc.cpu().numpy(), rec.cpu().numpy()
+        for (b, h), (q, k, v) in heads.items():
+            c, (rh, rt) = orc.arm_classify(q, k, ol, op, mode, 0.5)
+            assert abs(rec[b, h, 0] - rh) <= 1e-3 and abs(rec[b, h, 1] - rt) <= 1e-3, (b, h, rec[b, h], rh, rt)
+            if abs(rh - 0.5) >= 1e-3 and abs(rt - 0.5) >= 1e-3:
+                assert hc[b, h] == c, (b, h, hc[b, h], c, rh, rt)
+
+
+def test_force_dense_flag_ignores_the_classes():
+    w = inp.WORKLOADS["ragged128"]
+    print("case force-dense", flush=True)
+    rl, ol = lay(w)
+    rp = rf.rf_params(0.25, 0.25, 2, 0, rf.RF_FLAG_FORCE_DENSE)
+    Q, K, V = inp.full_qkv(w, DEV, 6.0)
+    ws = torch.empty(rf.rf_attention_workspace_bytes(w.B, w.nH, w.D, rl, rp), dtype=torch.uint8, device=DEV)
+    sparse_classes = torch.as_tensor(inp.round_robin_classes(w), dtype=torch.int32).to(DEV)
+    for hc, workspace in ((None, None), (sparse_classes, None), (sparse_classes, ws)):
+        O = rf.rf_sparse_attention(Q, K, V, hc, rl, rp, 128, workspace=workspace)
+        torch.cuda.synchronize()
+        for b in range(w.B):
+            for h in range(w.nH):
+                q, k, v = (f32(t) for t in inp.head_qkv(w, b, h, 6.0))
+                check(O[b, h], orc.attention(q, k, v, orc.DENSE, ol), "force-dense head(%d,%d)" % (b, h))
+    with pytest.raises(rf.RfError):  # without the flag the classes are required
+        rf.rf_sparse_attention(Q, K, V, None, rl, None, 128)
+
+
 # ----------------------------------------------------------------------------- ARM
 def arm_compare(w, Q, K, mode, alpha, rparams, oparams, heads=None):
     rl, ol = lay(w)

@@ -117,6 +117,36 @@ def test_textural_lists(lay, tau, block):
             assert (partial == ~full[qb, kbs]).all()
 
 
+@pytest.mark.parametrize("lay", [l for l in LAYOUTS if l[3] > 0])
+@pytest.mark.parametrize("block", [64, 128])
+def test_text_first_lists_are_over_the_video_first_order(lay, block):
+    """With the text tokens in front, the kernel still walks video tokens first: row r of the walked
+    order is tensor row  text_len + r  (video) or  r - Nv  (text).  The lists must match the oracle's
+    text-first mask brought into that order, and the gather tables must hold tensor rows."""
+    par = (0.25, 0.18, 3)
+    L, P = orc.Layout(*lay), orc.Params(par[0], par[1], par[2], text_first=True)
+    rl, rp = rf.rf_layout(*lay), rf.rf_params(par[0], par[1], par[2], 0, rf.RF_FLAG_TEXT_FIRST)
+    N, (T, H, W, tl) = orc.num_tokens(L), lay
+    Nv = T * H * W
+    row_of = np.r_[np.arange(Nv) + tl, np.arange(tl)]
+    for cls in (orc.SPATIAL, orc.TEMPORAL):
+        any_, full = brute_blocks(orc.keep_matrix(cls, L, P)[np.ix_(row_of, row_of)], block)
+        row_ptr, cols = rf.rf_plan_host(rl, rp, block, cls)
+        for qb in range(len(row_ptr) - 1):
+            ent = cols[row_ptr[qb]:row_ptr[qb + 1]]
+            kbs, partial = ent & ~rf.RF_PLAN_PARTIAL, (ent & rf.RF_PLAN_PARTIAL) != 0
+            assert set(kbs.tolist()) == set(np.nonzero(any_[qb])[0].tolist())
+            assert (partial == ~full[qb, kbs]).all()
+    tok = rf.rf_plan_position_major(rl, rp)
+    plain = rf.rf_plan_position_major(rl)
+    assert (tok == row_of[plain]).all() and sorted(tok.tolist()) == list(range(N))
+    # the flag is inert without text tokens
+    rl0 = rf.rf_layout(T, H, W, 0)
+    a = rf.rf_plan_host(rl0, rp, block, orc.TEMPORAL)
+    b = rf.rf_plan_host(rl0, rf.rf_params(par[0], par[1], par[2], 0), block, orc.TEMPORAL)
+    assert (a[0] == b[0]).all() and (a[1] == b[1]).all()
+
+
 @pytest.mark.parametrize("lay", LAYOUTS + [(33, 45, 80, 256), (13, 30, 45, 226)])
 @pytest.mark.parametrize("block", [64, 128, 256])
 def test_query_block_order_is_a_permutation(lay, block):
@@ -180,7 +210,7 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     assert attn(lay=rf.rf_layout(0, 8, 8, 0)) == -3 and attn(lay=rf.rf_layout(4, 8, 8, -1)) == -3
     assert attn(lay=rf.rf_layout(4096, 4096, 4096, 0)) in (-2, -3)
     assert attn(par=rf.rf_params(1.5, 0.25, 2, 0)) == -4 and attn(par=rf.rf_params(0.25, -0.1, 2, 0)) == -4
-    assert attn(par=rf.rf_params(0.25, 0.25, 2, 0, 2)) == -4  # unknown flag
+    assert attn(par=rf.rf_params(0.25, 0.25, 2, 0, 8)) == -4  # unknown flag
     assert attn(par=rf.rf_params(0.25, 0.25, 0, 0)) == -4 and attn(par=rf.rf_params(float("nan"), 0.25, 2, 0)) == -4
     assert attn(block=32) == -5 and attn(block=512) == -5 and attn(block=0) == -5
     need = rf.rf_attention_workspace_bytes(1, 2, 64, L)

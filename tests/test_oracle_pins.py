@@ -376,3 +376,50 @@ def test_two_head_mode_sends_unmatched_heads_to_dense():
         assert r2 == r3 and c2 == (DENSE if c3 == TEXTURAL else c3)
     c2, idx, _ = orc.arm_classify_plus(q, k, L, Params(two_head=True), orc.SAMPLE_FIRST_FRAME, 0.999, BWS)
     assert (c2, idx) == (DENSE, -1)
+
+
+# ---------------------------------------------------------------- text tokens in front of the video
+def test_text_first_mask_from_first_principles():
+    """With the text tokens first, token n >= text_len is video token n - text_len; the predicate is
+    rebuilt here from frames, rows and columns and compared entry by entry."""
+    L, tl = Layout(4, 3, 4, text_len=5), 5
+    HW, Nv, N = 12, 48, 53
+    P = Params(0.25, 0.25, 2, text_first=True)
+    n = np.arange(N)
+    is_text = n < tl
+    v = n - tl
+    f, p = v // HW, v % HW
+    y, x = p // 4, p % 4
+    either_text = is_text[:, None] | is_text[None, :]
+    want = {
+        SPATIAL: either_text | (np.abs(f[:, None] - f[None, :]) <= 1),
+        TEMPORAL: either_text | (np.abs(p[:, None] - p[None, :]) <= 3),
+        TEXTURAL: either_text | np.broadcast_to(((y - x) % 2 == 0)[None, :], (N, N)),
+        DENSE: np.ones((N, N), bool),
+    }
+    for cls, M in want.items():
+        assert (orc.keep_matrix(cls, L, P) == M).all(), cls
+
+
+def test_text_first_is_the_text_last_problem_rotated():
+    """Moving the text rows from the end to the front and setting the flag must give the same
+    attention rows (moved the same way), the same samples (shifted) and the same recalls."""
+    L, tl = Layout(3, 3, 4, text_len=6), 6
+    N, D = orc.num_tokens(L), 8
+    q, k, v = rand_head(N, D, 41, peaky=6.0)
+    front = np.r_[np.arange(N - tl, N), np.arange(N - tl)]  # new row i holds old row front[i]
+    for cls in (SPATIAL, TEMPORAL, TEXTURAL):
+        ref = orc.attention(q, k, v, cls, L, Params())
+        got = orc.attention(q[front], k[front], v[front], cls, L, Params(text_first=True))
+        np.testing.assert_allclose(got, ref[front], rtol=0, atol=1e-12)
+        # and it is SDPA under the explicit boolean mask of the rotated problem
+        M = orc.keep_matrix(cls, L, Params(text_first=True))
+        np.testing.assert_allclose(got, sdpa64(q[front], k[front], v[front], M), rtol=0, atol=1e-12)
+    for glob in (False, True):
+        assert (orc.sample_tokens(L, Params(text_first=True), glob) == orc.sample_tokens(L, Params(), glob) + tl).all()
+        for cls in (SPATIAL, TEMPORAL):
+            assert orc.arm_recall(q[front], k[front], L, Params(text_first=True), glob, cls) == pytest.approx(
+                orc.arm_recall(q, k, L, Params(), glob, cls), abs=1e-14)
+    # without text tokens the flag changes nothing
+    L0 = Layout(3, 3, 4)
+    assert (orc.keep_matrix(TEMPORAL, L0, Params(text_first=True)) == orc.keep_matrix(TEMPORAL, L0, Params())).all()
