@@ -6,6 +6,9 @@
 // |attr[a] - attr[b]| <= radius.  The scores Q'K'^T / sqrt(D) are formed tile by tile with
 // bf16 MFMA and never stored; per sampled query the kernel keeps a running maximum, the
 // softmax denominator over all sampled keys (M_init) and the part of it on kept keys (M').
+// The masks are bands on the attribute, so for most (32 queries, 64 keys) pairs every entry is
+// kept or every entry is dropped; the kernel tells from the attribute ranges of the two sides and
+// applies the mask entry by entry only where the band's edge crosses the pair.
 // Per-row recalls go to scratch and are reduced in a fixed order by arm_finish_kernel, which
 // also applies the decision rule.
 #include "rf_device.h"
@@ -19,7 +22,7 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
     constexpr int NW = kArmWaves, NT = 64 * NW, BQ = 32 * NW;
     using KT = KTile<D, NT>;
     __shared__ __attribute__((aligned(16))) unsigned char kbuf[2 * KT::BYTES];
-    __shared__ int abuf[2 * kTileK];
+    __shared__ int abuf[2 * (kTileK + 2)];  // per buffer: the tile's 64 attributes, then their minimum and maximum
 
     const int item = xcd_contiguous_item(blockIdx.x, nQB * 2 * a.BH);
     if (item < 0) return;
@@ -39,6 +42,15 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
     bf16x8 qf[D / 16];
     load_q_frags<D>(Qh, qsc * ps.stride, hf, qf);
     const int q_attr = ps.attr[qsc];
+    // attribute range of this wavefront's 32 queries (both halves hold the same queries)
+    int q_min = q_attr, q_max = q_attr;
+#pragma unroll
+    for (int w = 1; w < 32; w <<= 1) {
+        q_min = min(q_min, __shfl_xor(q_min, w, 64));
+        q_max = max(q_max, __shfl_xor(q_max, w, 64));
+    }
+    q_min = __builtin_amdgcn_readfirstlane(q_min);
+    q_max = __builtin_amdgcn_readfirstlane(q_max);
 
     float m_run = -INFINITY, l_all = 0.f, l_kept[kMaxBw];
 #pragma unroll
@@ -56,7 +68,20 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
     };
     auto stash_tile = [&](int t) {
         kt.stash(kbuf + (t & 1) * KT::BYTES, tid);
-        if (tid < kTileK) abuf[(t & 1) * kTileK + tid] = attr_reg;
+        if (tid < kTileK) {  // the first wavefront: attributes, and their range by a butterfly over its 64 lanes
+            int* ab = abuf + (t & 1) * (kTileK + 2);
+            ab[tid] = attr_reg;
+            int lo = attr_reg, hi = attr_reg;
+#pragma unroll
+            for (int w = 1; w < 64; w <<= 1) {
+                lo = min(lo, __shfl_xor(lo, w, 64));
+                hi = max(hi, __shfl_xor(hi, w, 64));
+            }
+            if (tid == 0) {
+                ab[kTileK] = lo;
+                ab[kTileK + 1] = hi;
+            }
+        }
     };
     fetch_tile(0);
     stash_tile(0);
@@ -65,7 +90,7 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
     for (int t = 0; t < ntiles; ++t) {
         if (t + 1 < ntiles) fetch_tile(t + 1);
         const unsigned char* kl = kbuf + (t & 1) * KT::BYTES;
-        const int* al = abuf + (t & 1) * kTileK;
+        const int* al = abuf + (t & 1) * (kTileK + 2);
         const int k0 = t * kTileK;
 
         f32x16 s[2];
@@ -89,20 +114,41 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
         float sum_all = 0.f, sum_kept[kMaxBw];
 #pragma unroll
         for (int b = 0; b < kMaxBw; ++b) sum_kept[b] = 0.f;
+        // Where does the band's edge fall for this (wavefront, tile) pair?  inside: bit b set if every
+        // pair is within radius b; mixed: some candidate has both kept and dropped pairs here.
+        const int k_min = __builtin_amdgcn_readfirstlane(al[kTileK]), k_max = __builtin_amdgcn_readfirstlane(al[kTileK + 1]);
+        const int reach = max(k_max - q_min, q_max - k_min), gap = max(k_min - q_max, q_min - k_max);
+        int inside = 0;
+        bool mixed = false;
 #pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2)
+        for (int b = 0; b < kMaxBw; ++b) {
+            if (b >= n_bw) break;
+            if (reach <= ps.radius[b]) inside |= 1 << b;
+            else if (gap <= ps.radius[b]) mixed = true;
+        }
+        if (!mixed) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = fast_exp2(fmaf(s[kb2][r], c, -mc));
-                const int d = q_attr - al[32 * kb2 + key_of_reg(r, hf)];
-                const int dist = d < 0 ? -d : d;
-                sum_all += p;
-                sum_kept[0] += dist <= ps.radius[0] ? p : 0.f;
-                if (n_bw > 1) {  // uniform: the per-head bandwidth variant measures every candidate at once
+            for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
-                    for (int b = 1; b < kMaxBw; ++b) sum_kept[b] += (b < n_bw && dist <= ps.radius[b]) ? p : 0.f;
+                for (int r = 0; r < 16; ++r) sum_all += fast_exp2(fmaf(s[kb2][r], c, -mc));
+#pragma unroll
+            for (int b = 0; b < kMaxBw; ++b) sum_kept[b] = ((inside >> b) & 1) ? sum_all : 0.f;
+        } else {
+#pragma unroll
+            for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float p = fast_exp2(fmaf(s[kb2][r], c, -mc));
+                    const int d = q_attr - al[32 * kb2 + key_of_reg(r, hf)];
+                    const int dist = d < 0 ? -d : d;
+                    sum_all += p;
+                    sum_kept[0] += dist <= ps.radius[0] ? p : 0.f;
+                    if (n_bw > 1) {  // uniform: the per-head bandwidth variant measures every candidate at once
+#pragma unroll
+                        for (int b = 1; b < kMaxBw; ++b) sum_kept[b] += (b < n_bw && dist <= ps.radius[b]) ? p : 0.f;
+                    }
                 }
-            }
+        }
         l_all = l_all * alpha + sum_all;
 #pragma unroll
         for (int b = 0; b < kMaxBw; ++b) l_kept[b] = l_kept[b] * alpha + sum_kept[b];
