@@ -374,18 +374,13 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
             }
         }
     };
-    // p = exp2((s - m_ref) * c) in place; returns this lane's sum
+    // p = exp2((s - m_ref) * c) in place
     auto exponentiate = [&](f32x16 (&s)[2]) {
         const float mc = m_ref * c;
-        float sum = 0.f;
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                s[kb2][r] = fast_exp2(fmaf(s[kb2][r], c, -mc));
-                sum += s[kb2][r];
-            }
-        return sum;
+            for (int r = 0; r < 16; ++r) s[kb2][r] = fast_exp2(fmaf(s[kb2][r], c, -mc));
     };
 
     // O^T += V^T P^T for tile t, P (bf16) in pf
@@ -469,9 +464,9 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
                 has_ref = true;
             }
         }
-        const float psum = exponentiate(s);
-        l_run += psum;
-
+        exponentiate(s);
+        // P is rounded to bf16 for the second MFMA; the denominator sums those same rounded values
+        // (two per v_dot2c_f32_bf16), so numerator and denominator of Eq. 2 see identical weights
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
@@ -481,6 +476,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
                 w.y = pack_bf16(s[kb2][8 * u2 + 2], s[kb2][8 * u2 + 3]);
                 w.z = pack_bf16(s[kb2][8 * u2 + 4], s[kb2][8 * u2 + 5]);
                 w.w = pack_bf16(s[kb2][8 * u2 + 6], s[kb2][8 * u2 + 7]);
+                l_run = add_bf16_pair(add_bf16_pair(add_bf16_pair(add_bf16_pair(l_run, w.x), w.y), w.z), w.w);
                 pf[2 * kb2 + u2] = as_bf16x8(w);
             }
         accumulate(t);

@@ -36,6 +36,12 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+// acc + lo + hi of a packed pair of bf16 values, in fp32 (v_dot2c_f32_bf16 against {1, 1})
+__device__ __forceinline__ float add_bf16_pair(float acc, uint32_t pair) {
+    const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), ones, acc, false);
+}
+
 __device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 64); }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
