@@ -183,12 +183,18 @@ int rf_plan_host(const rf_layout *layout, const rf_params *params, int block, in
                  int32_t *row_ptr, int32_t *cols, size_t cap, size_t *needed);
 
 /*
- * Host-side view of the order in which rf_sparse_attention hands a head's query blocks to
- * workgroups under pattern `cls` (a scheduling detail: it affects cache behaviour and load
- * balance, never the result).  order: host, int32 [nQB], receives a permutation of 0..nQB-1.
- * RF_DENSE heads use the identity.
+ * Host-side view of how rf_sparse_attention schedules a head's query blocks under pattern `cls`
+ * (scheduling only: it affects cache behaviour and load balance, never the result).
+ *   order       : host, int32 [nQB], receives a permutation of 0..nQB-1: the order in which blocks are
+ *                 handed out (identity for RF_DENSE); XCD x of the GPU runs entries
+ *                 [x * ceil(nQB/8), (x+1) * ceil(nQB/8)) of it.
+ *   first_entry : host, int32 [nQB] or NULL: per query block, the entry of its rf_plan_host list at
+ *                 which its walk starts (it wraps around), chosen so that blocks in flight together
+ *                 on an XCD sweep the same key tiles at the same time; 0 where the list is not one
+ *                 sliding range of tiles.
  */
-int rf_plan_order(const rf_layout *layout, const rf_params *params, int block, int cls, int32_t *order);
+int rf_plan_order(const rf_layout *layout, const rf_params *params, int block, int cls, int32_t *order,
+                  int32_t *first_entry);
 
 /* Position-major order of the tokens: token_of (host, int32 [N]) receives, for every row of that
  * order, the token (row of the caller's tensors) it holds: video token (frame f, in-frame position

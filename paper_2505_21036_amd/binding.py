@@ -81,7 +81,7 @@ def load_library():
     lib.rf_plan_host.restype = C.c_int
     lib.rf_plan_host.argtypes = [PL, PP, C.c_int, C.c_int, vp, vp, C.c_size_t, C.POINTER(C.c_size_t)]
     lib.rf_plan_order.restype = C.c_int
-    lib.rf_plan_order.argtypes = [PL, PP, C.c_int, C.c_int, vp]
+    lib.rf_plan_order.argtypes = [PL, PP, C.c_int, C.c_int, vp, vp]
     lib.rf_plan_position_major.restype = C.c_int
     lib.rf_plan_position_major.argtypes = [PL, PP, vp]
     lib.rf_plan_clear.restype = C.c_int
@@ -246,14 +246,17 @@ def rf_plan_host(layout, params, block, cls):
     return row_ptr, cols[:needed.value]
 
 
-def rf_plan_order(layout, params, block, cls):
-    """Order in which a head's query blocks are handed to workgroups: int32 permutation of 0..nQB-1."""
+def rf_plan_order(layout, params, block, cls, full=False):
+    """Order in which a head's query blocks are handed to workgroups: int32 permutation of 0..nQB-1.
+    full=True: (order, first_entry int32 [nQB])."""
     N = layout.T * layout.H * layout.W + layout.text_len
-    order = np.full((N + block - 1) // block, -1, dtype=np.int32)
-    st = load_library().rf_plan_order(C.byref(layout), _pp(params), block, cls, order.ctypes.data)
+    nqb = (N + block - 1) // block
+    order = np.full(nqb, -1, dtype=np.int32)
+    first = np.full(nqb, -1, dtype=np.int32)
+    st = load_library().rf_plan_order(C.byref(layout), _pp(params), block, cls, order.ctypes.data, first.ctypes.data)
     if st != 0:
         raise RfError(st, "rf_plan_order")
-    return order
+    return (order, first) if full else order
 
 
 def rf_plan_position_major(layout, params=None):

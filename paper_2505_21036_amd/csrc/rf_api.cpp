@@ -69,12 +69,13 @@ int get_attention_plan(const Geometry& g, int block, const DevicePlan** out) {
         HostPlan hp;
         build_plan(g, block, &hp);
         BlobBuilder bb;
-        size_t off_rp[kLists], off_co[kLists], off_at[kLists], off_qo[kLists];
+        size_t off_rp[kLists], off_co[kLists], off_at[kLists], off_qo[kLists], off_fe[kLists];
         for (int c = 0; c < kLists; ++c) {
             off_rp[c] = bb.add(hp.row_ptr[c]);
             off_co[c] = bb.add(hp.cols[c]);
             off_at[c] = bb.add(hp.attr[c]);
             off_qo[c] = bb.add(hp.qorder[c]);
+            off_fe[c] = bb.add(hp.first_entry[c]);
         }
         const size_t off_ci = bb.add(hp.cidx), off_pm = bb.add(hp.pm_token);
         auto p = std::make_unique<CachedPlan>();
@@ -90,6 +91,7 @@ int get_attention_plan(const Geometry& g, int block, const DevicePlan** out) {
             d.cols[c] = base + off_co[c];
             d.attr[c] = base + off_at[c];
             d.qorder[c] = base + off_qo[c];
+            d.first_entry[c] = base + off_fe[c];
         }
         d.cidx = base + off_ci;
         d.pm_token = base + off_pm;
@@ -142,6 +144,32 @@ int get_arm_tables(const Geometry& g, const CachedPlan** out) {
         g_plans.push_back(std::move(p));
     }
     *out = cp;
+    return RF_OK;
+}
+
+// Work-queue counters of the attention kernel: 8 ints per call, taken round-robin from a small
+// per-device ring so that calls in flight on different streams do not share a set.
+constexpr int kQueueSets = 64, kQueueStride = 64;  // ints; a set per 256 bytes
+struct QueueRing {
+    int device;
+    int* base;
+    unsigned next;
+};
+std::vector<QueueRing> g_queues;
+
+int next_queue(int** out) {
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return RF_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_mu);
+    for (auto& r : g_queues)
+        if (r.device == device) {
+            *out = r.base + (r.next++ % kQueueSets) * kQueueStride;
+            return RF_OK;
+        }
+    void* p = nullptr;
+    if (hipMalloc(&p, kQueueSets * kQueueStride * sizeof(int)) != hipSuccess) return RF_ERR_HIP;
+    g_queues.push_back(QueueRing{device, static_cast<int*>(p), 1});
+    *out = static_cast<int*>(p);
     return RF_OK;
 }
 
@@ -320,6 +348,8 @@ static int sparse_attention_impl(const void* Q, const void* K, const void* V, co
     a.K = static_cast<const uint16_t*>(K);
     a.V = static_cast<const uint16_t*>(V);
     a.O = static_cast<uint16_t*>(O);
+    st = next_queue(&a.queue);
+    if (st != RF_OK) return st;
     a.head_class = force_dense ? nullptr : head_class;
     a.head_bw = bandwidths ? head_bw : nullptr;
     a.BH = B * nH;
@@ -371,7 +401,8 @@ int rf_plan_host(const rf_layout* layout, const rf_params* params, int block, in
     return RF_OK;
 }
 
-int rf_plan_order(const rf_layout* layout, const rf_params* params, int block, int cls, int32_t* order) {
+int rf_plan_order(const rf_layout* layout, const rf_params* params, int block, int cls, int32_t* order,
+                  int32_t* first_entry) {
     if (!layout || !order) return RF_ERR_NULL;
     Geometry g;
     const int st = resolve_geometry(layout, params, &g);
@@ -382,6 +413,8 @@ int rf_plan_order(const rf_layout* layout, const rf_params* params, int block, i
     build_plan(g, block, &hp);
     const int list = cls == RF_LIST_TEMPORAL_POSITION_MAJOR ? kListTemporalPM : cls;
     for (int i = 0; i < hp.nQB; ++i) order[i] = cls == RF_DENSE ? i : hp.qorder[list][i];
+    if (first_entry)
+        for (int i = 0; i < hp.nQB; ++i) first_entry[i] = cls == RF_DENSE ? 0 : hp.first_entry[list][i];
     return RF_OK;
 }
 
@@ -397,12 +430,15 @@ int rf_plan_position_major(const rf_layout* layout, const rf_params* params, int
 
 int rf_plan_clear(void) {
     std::lock_guard<std::mutex> lock(g_mu);
-    if (g_plans.empty()) return RF_OK;
+    if (g_plans.empty() && g_queues.empty()) return RF_OK;
     int st = RF_OK;
     if (hipDeviceSynchronize() != hipSuccess) st = RF_ERR_HIP;
     for (auto& p : g_plans)
         if (p->blob && hipFree(p->blob) != hipSuccess) st = RF_ERR_HIP;
     g_plans.clear();
+    for (auto& r : g_queues)
+        if (hipFree(r.base) != hipSuccess) st = RF_ERR_HIP;
+    g_queues.clear();
     return st;
 }
 

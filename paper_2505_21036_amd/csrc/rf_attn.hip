@@ -6,6 +6,8 @@
 // score tile with bf16 MFMA, runs the online softmax in fp32 with exp2, and accumulates
 // O^T = V^T P^T with bf16 MFMA.  In tiles flagged partial the token-level predicate of the
 // pattern is re-applied to each score.
+#include <algorithm>
+
 #include "rf_device.h"
 
 namespace rf {
@@ -219,6 +221,7 @@ struct QueryBlock {
     // tokens come first in the tensors, and 0 when kbase/vbase are packed copies (already in walked order)
     int video_shift, text_shift;
     const int32_t* cols;  // MODE_LISTED: this query block's tile entries
+    int first;            // MODE_LISTED: entry the (cyclic) walk starts at
     int ntiles;           // key tiles to visit
     int keyN;             // length of the key sequence walked (N, or Nc when compacted)
 };
@@ -276,7 +279,10 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
     // Tile entries of a listed query block are read 64 at a time, one per lane, and handed out with
     // v_readlane: no scalar-load latency in the loop.  ent_cur covers [ent_base, ent_base + 64).
     int ent_cur = 0, ent_nxt = 0, ent_base = 0;
-    auto load_entries = [&](int first) { return qk.cols[min(first + lane, ntiles - 1)]; };
+    auto load_entries = [&](int from) {
+        const int j = min(from + lane, ntiles - 1) + qk.first;  // the walk starts at entry qk.first and wraps
+        return qk.cols[j < ntiles ? j : j - ntiles];
+    };
     if (MODE == MODE_LISTED && ntiles > 0) {
         ent_cur = load_entries(0);
         ent_nxt = load_entries(64);
@@ -507,24 +513,92 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
     }
 }
 
+#ifdef RF_TRACE
+// Diagnostic build only: per workgroup, wall-clock ticks (100 MHz) at entry and exit and the
+// number of tiles walked, into a buffer set with rf_debug_set_trace().
+__device__ unsigned long long* g_trace = nullptr;
+extern "C" int rf_debug_set_trace(void* p) { return static_cast<int>(hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &p, sizeof(p))); }
+#endif
+
 // Wavefronts per SIMD the register allocation is held to: three for head_dim 64 with 128-row
 // blocks (measured best; its accumulators are half the size), two otherwise.
 constexpr int attn_waves_per_simd(int D, int NW) { return (D == 64 && NW == 4) ? 3 : 2; }  // NW = 8: one workgroup per CU
 
+// The next (head, query block) item for a workgroup whose home queue is `home`, or -1 when every
+// queue is empty.  Queue x holds, head after head, the ordinals [x * per_xcd, (x+1) * per_xcd) of
+// the block order; ctr[x] counts how many of its items have been handed out.  A workgroup drains its
+// home queue first (its neighbours on the XCD are on the same part of the same head, which is what
+// the L2 wants) and then helps whichever queue has the most left.  Every path ends: counters only
+// grow, a failed take means another workgroup took that item, and once all are taken -1 is returned.
+__device__ __forceinline__ int take_item(int* ctr, int home, int BH, int nQB, int per_xcd, int* queue) {
+    auto items = [&](int x) { return max(0, min(per_xcd, nQB - x * per_xcd)) * BH; };
+    auto taken = [&](int x) { return __hip_atomic_load(ctr + x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+    int q = home;
+    for (;;) {
+        if (taken(q) < items(q)) {
+            const int j = __hip_atomic_fetch_add(ctr + q, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (j < items(q)) {
+                *queue = q;
+                return j;
+            }
+        }
+        int best = -1, best_left = 0;
+        for (int x = 0; x < 8; ++x) {
+            const int left = items(x) - taken(x);
+            if (left > best_left) {
+                best_left = left;
+                best = x;
+            }
+        }
+        if (best < 0) return -1;
+        q = best;
+    }
+}
+
+template <int D, int NW>
+__device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xcd, int nQB, int per_xcd, unsigned char* smem);
+
+__global__ void reset_queue_kernel(int* ctr) {
+    if (threadIdx.x < 8) ctr[threadIdx.x] = 0;
+}
+
 template <int D, int NW>
 __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(attn_waves_per_simd(D, NW), attn_waves_per_simd(D, NW)))) attn_kernel(AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    // Workgroup ids go to the 8 XCDs round-robin.  Every XCD takes one eighth of a head's query
-    // blocks, a contiguous run of the pattern's block order (neighbours in that order walk nearly
-    // the same key tiles, which they then share through the XCD's L2), and all XCDs move through
-    // the heads together, so the K/V of the head in flight (tens of MB) stays resident in the
-    // memory-side cache for whatever misses L2.
+    __shared__ int item_box[2];
+    // A resident set of workgroups (as many as fit on the chip) works through the (head, query
+    // block) items.  Workgroup ids go to the 8 XCDs round-robin; XCD x's queue is one eighth of every
+    // head's block order, head after head (neighbours in that order walk nearly the same key tiles,
+    // which they share through the XCD's L2), so all XCDs move through the heads together and the
+    // K/V of the head in flight (tens of MB) stays resident in the memory-side cache for whatever
+    // misses L2.  XCDs differ in speed by several per cent and shares in work; an XCD whose queue is
+    // empty takes items from the others.
     const int nQB = a.plan[0].nQB, per_xcd = (nQB + 7) >> 3;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int ordinal = xcd * per_xcd + slot % per_xcd;
-    if (ordinal >= nQB) return;
+    for (;;) {
+        if (threadIdx.x == 0) {
+            int q = 0;
+            item_box[0] = take_item(a.queue, blockIdx.x & 7, a.BH, nQB, per_xcd, &q);
+            item_box[1] = q;
+        }
+        __syncthreads();
+        // wavefront-uniform by construction; say so, so that everything derived stays in scalar registers
+        const int item = __builtin_amdgcn_readfirstlane(item_box[0]), xcd = __builtin_amdgcn_readfirstlane(item_box[1]);
+        __syncthreads();
+        if (item < 0) break;
+        process_item<D, NW>(a, item, xcd, nQB, per_xcd, smem);
+    }
+}
+
+// One (head, query block) item: item-th of queue xcd.
+template <int D, int NW>
+__device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xcd, int nQB, int per_xcd, unsigned char* smem) {
+    const int share = max(0, min(per_xcd, nQB - xcd * per_xcd));
+    const int ordinal = xcd * per_xcd + item % share;
+#ifdef RF_TRACE
+    const unsigned long long trace_t0 = wall_clock64();
+#endif
     QueryBlock qk;
-    qk.bh = slot / per_xcd;
+    qk.bh = item / share;
     // per-head bandwidth: the plans differ only in the Spatial / Temporal lists, radii and block order
     int which = 0;
     if (a.head_bw) {
@@ -539,6 +613,7 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
     const bool temporal_pm = cls == RF_TEMPORAL && a.packed_k;
     const int list = temporal_pm ? kListTemporalPM : cls;
     qk.qb = cls == RF_DENSE ? ordinal : pl.qorder[list][ordinal];
+    qk.first = 0;
     qk.cols = nullptr;
     qk.list = cls;
     qk.row_token = nullptr;
@@ -577,9 +652,21 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
         const int e0 = pl.row_ptr[list][qk.qb];
         qk.ntiles = pl.row_ptr[list][qk.qb + 1] - e0;
         qk.cols = pl.cols[list] + e0;
+#ifndef RF_NO_ROTATE
+        qk.first = pl.first_entry[list][qk.qb];
+#endif
         qk.keyN = pl.N;
         attend<D, NW, MODE_LISTED>(a, pl, qk, smem);
     }
+#ifdef RF_TRACE
+    if (g_trace && threadIdx.x == 0) {
+        unsigned long long* rec = g_trace + 4 * (static_cast<size_t>(qk.bh) * nQB + ordinal);
+        rec[0] = trace_t0;
+        rec[1] = wall_clock64();
+        rec[2] = (static_cast<unsigned long long>(blockIdx.x) << 32) | static_cast<unsigned>(qk.ntiles);
+        rec[3] = (static_cast<unsigned long long>(xcd) << 32) | static_cast<unsigned>(qk.qb);
+    }
+#endif
 }
 
 // Copies of K and V in the order their head walks them, into the caller's workspace: for a
@@ -618,14 +705,24 @@ template <int D, int NW>
 static int launch_one(const AttnArgs& a, hipStream_t st) {
     constexpr int NT = 64 * NW;
     constexpr int smem = AttnSmem<D, NW>::BYTES;
-    static bool configured = false;  // raising the dynamic-LDS limit is per function, once
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<D, NW>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    static int resident = 0;  // workgroups the chip holds at once; set on first use (also raises the dynamic-LDS limit)
+    if (resident == 0) {
+        const void* fn = reinterpret_cast<const void*>(&attn_kernel<D, NW>);
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return static_cast<int>(e);
-        configured = true;
+        int dev = 0, cus = 0, per_cu = 0;
+        if ((e = hipGetDevice(&dev)) != hipSuccess) return static_cast<int>(e);
+        if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return static_cast<int>(e);
+        if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_kernel<D, NW>, NT, smem)) != hipSuccess)
+            return static_cast<int>(e);
+        if (cus < 1 || per_cu < 1) return static_cast<int>(hipErrorInvalidValue);
+        resident = cus * per_cu;
     }
-    const int grid = 8 * ((a.plan[0].nQB + 7) / 8) * a.BH;
+    const long long items = static_cast<long long>(a.plan[0].nQB) * a.BH;
+    const int grid = static_cast<int>(std::min<long long>(resident, items));
+    hipLaunchKernelGGL(reset_queue_kernel, dim3(1), dim3(64), 0, st, a.queue);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return static_cast<int>(e);
     hipLaunchKernelGGL((attn_kernel<D, NW>), dim3(grid), dim3(NT), smem, st, a);
     return static_cast<int>(hipGetLastError());
 }

@@ -50,7 +50,12 @@ struct HostPlan {
     int first_text_qb;  // first query block holding a text row (nQB if there is none)
     // CSR lists of key tiles per query block; Textural: text-holding query blocks only
     std::vector<int32_t> row_ptr[kLists], cols[kLists];
-    std::vector<int32_t> qorder[kLists];  // order in which a head's query blocks are handed out (a permutation)
+    // Scheduling of a head's query blocks (affects cache behaviour only, never the result), per list:
+    // qorder = the order in which blocks are handed out (a permutation; XCD x takes ordinals
+    // [x * ceil(nQB/8), (x+1) * ceil(nQB/8)) of it), first_entry = the entry of its list a block starts
+    // its (cyclic) walk at.
+    std::vector<int32_t> qorder[kLists];
+    std::vector<int32_t> first_entry[kLists];
     // per row of the list's order: frame index / in-frame index / 0 if kept by Eq. 4 else 1 / in-frame index
     std::vector<int32_t> attr[kLists];
     std::vector<int32_t> cidx;      // compacted position -> tensor row (Textural)
@@ -72,6 +77,7 @@ struct DevicePlan {
     const int32_t* cols[kLists];
     const int32_t* attr[kLists];
     const int32_t* qorder[kLists];
+    const int32_t* first_entry[kLists];
     const int32_t* cidx;
     const int32_t* pm_token;
     int radius[kLists];
@@ -94,6 +100,7 @@ struct AttnArgs {
     uint16_t* packed_k;
     uint16_t* packed_v;
     const int32_t* head_bw;  // optional per-head index into plan[]; null or out of range: plan[0]
+    int* queue;              // 8 work-queue counters (one per XCD), library-owned, zeroed by the launcher
     int n_plans;
     DevicePlan plan[kMaxBw];
 };

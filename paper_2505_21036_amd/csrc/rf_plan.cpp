@@ -65,20 +65,28 @@ inline int span_reach(Span a, Span b) { return std::max(b.hi - a.lo, a.hi - b.lo
 
 }  // namespace
 
-// Order in which a head's query blocks are handed to workgroups (the kernel gives XCD x the
-// ordinals [x * ceil(nQB/8), (x+1) * ceil(nQB/8)) of this order, and all XCDs advance together).
-// Two aims: blocks that run at the same time should walk the same key tiles, and the eight
-// shares should hold equal work.  Blocks are first put in a locality order (token order; under
-// the Temporal pattern, whose lists depend only on the in-frame position, grouped by position
-// across frames), cut into short runs, and the runs are dealt longest-first to the share with
-// the least work that still has room.
+// How a head's query blocks are handed to workgroups.  The attention kernel runs one queue of
+// (head, query block) items per XCD (each XCD has its own L2): XCD x owns the ordinals
+// [x * ceil(nQB/8), (x+1) * ceil(nQB/8)) of the order built here, head after head, and takes items
+// from other XCDs' queues once its own is empty, so the shares need not hold equal work.  What the
+// order must provide is locality: blocks that run together (an XCD has about kConcurrentRows query
+// rows in flight, a generation) should walk the same key tiles at the same time, so that a tile is
+// fetched into the XCD's L2 once.  Hence:
+//  - token order; under the Temporal pattern in token order, whose lists depend only on the
+//    in-frame position, blocks are grouped by position across frames;
+//  - in the banded lists (Spatial; Temporal in position-major order) a block's tiles are one
+//    contiguous range that slides with the block, so the blocks of a generation all start their
+//    walk at the same tile, the first tile of the generation's last block, and wrap around: they
+//    then sweep the same tiles in step instead of each trailing its neighbour by the slide.
 static void order_query_blocks(HostPlan* plan) {
     HostPlan& P = *plan;
     const int nQB = P.nQB, block = P.block, HW = P.g.HW, Nv = P.g.Nv;
     const int per_share = (nQB + 7) / 8;
-    constexpr int kRunBlocks = 8;
+    constexpr int kConcurrentRows = 8192;  // 32 CUs x 256 rows
+    const int generation = std::max(1, kConcurrentRows / block);
     for (int cls = 0; cls < kLists; ++cls) {
-        std::vector<int32_t> ord(nQB);
+        std::vector<int32_t>& ord = P.qorder[cls];
+        ord.resize(nQB);
         for (int qb = 0; qb < nQB; ++qb) ord[qb] = qb;
         if (cls == RF_TEMPORAL) {
             auto key = [&](int qb) {
@@ -87,46 +95,25 @@ static void order_query_blocks(HostPlan* plan) {
             };
             std::stable_sort(ord.begin(), ord.end(), [&](int a, int b) { return key(a) < key(b); });
         }
-        auto work = [&](int qb) -> int64_t {
-            if (cls == RF_TEXTURAL && qb < P.first_text_qb) return P.nCT;
-            return P.row_ptr[cls][qb + 1] - P.row_ptr[cls][qb];
-        };
-        struct Run { int first, len; int64_t work; };
-        std::vector<Run> runs;
-        for (int i = 0; i < nQB; i += kRunBlocks) {
-            Run r{i, std::min(kRunBlocks, nQB - i), 0};
-            for (int j = 0; j < r.len; ++j) r.work += work(ord[i + j]);
-            runs.push_back(r);
-        }
-        std::vector<int> by_work(runs.size());
-        for (size_t i = 0; i < runs.size(); ++i) by_work[i] = static_cast<int>(i);
-        std::stable_sort(by_work.begin(), by_work.end(), [&](int a, int b) { return runs[a].work > runs[b].work; });
-        std::vector<std::vector<int>> share(8);  // run indices per share
-        int64_t load[8] = {0};
-        int room[8];
-        for (int x = 0; x < 8; ++x) room[x] = std::max(0, std::min(per_share, nQB - x * per_share));
-        std::vector<int32_t> leftovers;  // blocks of runs that had to be split
-        for (int ri : by_work) {
-            int best = -1;
-            for (int x = 0; x < 8; ++x)
-                if (room[x] >= runs[ri].len && (best < 0 || load[x] < load[best])) best = x;
-            if (best < 0) {
-                for (int j = 0; j < runs[ri].len; ++j) leftovers.push_back(ord[runs[ri].first + j]);
-                continue;
+        std::vector<int32_t>& fe = P.first_entry[cls];
+        fe.assign(nQB, 0);
+        if (cls != RF_SPATIAL && cls != kListTemporalPM) continue;
+        auto tile_of = [&](int e) { return P.cols[cls][e] & kTileIndexMask; };
+        for (int s0 = 0; s0 < nQB; s0 += per_share)
+            for (int g0 = s0; g0 < std::min(s0 + per_share, nQB); g0 += generation) {
+                const int g1 = std::min({g0 + generation, s0 + per_share, nQB});
+                int start_tile = 0;
+                for (int o = g0; o < g1; ++o) {
+                    const int qb = ord[o];
+                    if (P.row_ptr[cls][qb] < P.row_ptr[cls][qb + 1]) start_tile = std::max(start_tile, tile_of(P.row_ptr[cls][qb]));
+                }
+                for (int o = g0; o < g1; ++o) {
+                    const int qb = ord[o], e0 = P.row_ptr[cls][qb], e1 = P.row_ptr[cls][qb + 1];
+                    int e = e0;
+                    while (e < e1 && tile_of(e) < start_tile) ++e;
+                    fe[qb] = e < e1 ? e - e0 : 0;
+                }
             }
-            share[best].push_back(ri);
-            load[best] += runs[ri].work;
-            room[best] -= runs[ri].len;
-        }
-        std::vector<int32_t>& out = P.qorder[cls];
-        out.clear();
-        size_t lo = 0;
-        for (int x = 0; x < 8; ++x) {
-            std::sort(share[x].begin(), share[x].end());  // keep neighbouring runs next to each other
-            for (int ri : share[x])
-                for (int j = 0; j < runs[ri].len; ++j) out.push_back(ord[runs[ri].first + j]);
-            for (; room[x] > 0 && lo < leftovers.size(); --room[x]) out.push_back(leftovers[lo++]);
-        }
     }
 }
 

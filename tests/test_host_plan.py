@@ -158,16 +158,44 @@ def test_query_block_order_is_a_permutation(lay, block):
     assert (rf.rf_plan_order(rl, None, block, rf.RF_DENSE) == np.arange(nqb)).all()
 
 
-def test_query_block_order_balances_the_eight_shares():
-    """At the 720p shape each XCD's share of a head carries about the same number of key tiles."""
+def test_query_block_order_keeps_neighbours_together():
+    """The XCD queues are eighths of the order; blocks next to each other in it must be neighbours in
+    the sequence (token order, or position-grouped for Temporal in token order)."""
     rl = rf.rf_layout(33, 45, 80, 256)
-    for cls in (rf.RF_SPATIAL, rf.RF_TEMPORAL):
-        row_ptr, _ = rf.rf_plan_host(rl, None, 128, cls)
-        work = np.diff(row_ptr)
-        order = rf.rf_plan_order(rl, None, 128, cls)
+    for block in (128, 256):
+        for cls in (rf.RF_SPATIAL, rf.RF_TEXTURAL, rf.RF_DENSE, rf.RF_LIST_TEMPORAL_POSITION_MAJOR):
+            order, first = rf.rf_plan_order(rl, None, block, cls, full=True)
+            assert (order == np.arange(len(order))).all()
+            work = np.diff(rf.rf_plan_host(rl, None, block, cls)[0])
+            assert ((first >= 0) & (first < np.maximum(work, 1))).all()
+        order = rf.rf_plan_order(rl, None, block, rf.RF_TEMPORAL)
+        pos = (order.astype(np.int64) * block) % (45 * 80) // block
+        video = order.astype(np.int64) * block < 33 * 45 * 80
+        assert (np.diff(pos[video]) >= 0).all() and video[:video.sum()].all()  # grouped by in-frame position, text last
+
+
+@pytest.mark.parametrize("lay", [(7, 10, 13, 50), (33, 45, 80, 256)])
+def test_blocks_of_a_generation_start_at_a_common_tile(lay):
+    """Banded lists: the blocks an XCD runs together (32 blocks of 256 rows out of its eighth of the
+    order) begin their cyclic walk at the same key tile wherever their lists hold it."""
+    rl = rf.rf_layout(*lay)
+    block = 256
+    for cls in (rf.RF_SPATIAL, rf.RF_LIST_TEMPORAL_POSITION_MAJOR):
+        row_ptr, cols = rf.rf_plan_host(rl, None, block, cls)
+        order, first = rf.rf_plan_order(rl, None, block, cls, full=True)
+        tiles = cols & ~rf.RF_PLAN_PARTIAL
         per = -(-len(order) // 8)
-        loads = [work[order[x * per:(x + 1) * per]].sum() for x in range(8)]
-        assert max(loads) <= 1.03 * (sum(loads) / 8), loads
+        for s0 in range(0, len(order), per):
+            for g0 in range(s0, min(s0 + per, len(order)), 32):
+                blocks = order[g0:min(g0 + 32, s0 + per, len(order))]
+                lo = max(tiles[row_ptr[b]] for b in blocks)
+                for b in blocks:
+                    mine = tiles[row_ptr[b]:row_ptr[b + 1]]
+                    start = mine[first[b]]
+                    assert start == lo if lo in mine else first[b] == 0 or start > lo
+    # lists that are not one sliding range keep the plain walk
+    _, first = rf.rf_plan_order(rl, None, block, rf.RF_TEMPORAL, full=True)
+    assert (first == 0).all()
 
 
 def test_paper_shapes_executed_fractions():
