@@ -73,7 +73,8 @@ inline int span_reach(Span a, Span b) { return std::max(b.hi - a.lo, a.hi - b.lo
 // rows in flight, a generation) should walk the same key tiles at the same time, so that a tile is
 // fetched into the XCD's L2 once.  Hence:
 //  - token order; under the Temporal pattern in token order, whose lists depend only on the
-//    in-frame position, blocks are grouped by position across frames;
+//    in-frame position, blocks are grouped by position across frames; under the Textural pattern
+//    the blocks with text rows (the only ones that differ) come first;
 //  - in the banded lists (Spatial; Temporal in position-major order) a block's tiles are one
 //    contiguous range that slides with the block, so the blocks of a generation all start their
 //    walk at the same tile, the first tile of the generation's last block, and wrap around: they
@@ -94,6 +95,11 @@ static void order_query_blocks(HostPlan* plan) {
                 return q0 < Nv ? (q0 % HW) / block : (HW / block + 1);  // blocks that start in the text go last
             };
             std::stable_sort(ord.begin(), ord.end(), [&](int a, int b) { return key(a) < key(b); });
+        }
+        if (cls == RF_TEXTURAL) {
+            // the few blocks that hold text rows walk the whole sequence, twice the work of the others:
+            // hand them out first, so that they are not what the end of the launch waits for
+            std::stable_partition(ord.begin(), ord.end(), [&](int qb) { return qb >= P.first_text_qb; });
         }
         std::vector<int32_t>& fe = P.first_entry[cls];
         fe.assign(nQB, 0);

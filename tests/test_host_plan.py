@@ -165,7 +165,12 @@ def test_query_block_order_keeps_neighbours_together():
     for block in (128, 256):
         for cls in (rf.RF_SPATIAL, rf.RF_TEXTURAL, rf.RF_DENSE, rf.RF_LIST_TEMPORAL_POSITION_MAJOR):
             order, first = rf.rf_plan_order(rl, None, block, cls, full=True)
-            assert (order == np.arange(len(order))).all()
+            if cls == rf.RF_TEXTURAL:  # blocks holding text rows (twice the work) first, then token order
+                n_text = len(order) - 33 * 45 * 80 // block
+                assert (order[:n_text] == np.arange(len(order) - n_text, len(order))).all()
+                assert (order[n_text:] == np.arange(len(order) - n_text)).all()
+            else:
+                assert (order == np.arange(len(order))).all()
             work = np.diff(rf.rf_plan_host(rl, None, block, cls)[0])
             assert ((first >= 0) & (first < np.maximum(work, 1))).all()
         order = rf.rf_plan_order(rl, None, block, rf.RF_TEMPORAL)
