@@ -13,7 +13,10 @@
  *     them under RF_FLAG_TEXT_FIRST.  N = T*H*W + text_len.
  *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) and never synchronise it, except that the first call for a new
- *     (layout, params, block) builds and uploads its block lists synchronously.
+ *     (layout, params, block) builds and uploads its block lists synchronously.  After
+ *     such a warm-up call a sequence of calls only launches kernels (no memsets, no
+ *     allocations) and can be captured into a HIP graph; results are bitwise the same
+ *     from call to call.
  *   - Return value: RF_OK or a negative rf_status.  Arguments are validated before
  *     any GPU work, so a bad argument never launches a kernel.
  *   - `params == NULL` selects the paper's defaults (Sec. 4.1: both bandwidths 1/4,

@@ -367,3 +367,76 @@ def test_hunyuan720p_headline_layer():
     # property at full size: constant values must come back as that constant on every row
     O = run_attention(w, Q, K, torch.ones_like(V), classes, w.block)
     assert (O.float() - 1).abs().max().item() <= 1e-2
+
+
+# ----------------------------------------------------------------------------- graphs and streams
+def test_step_replays_from_a_hip_graph():
+    """ARM + attention captured once (after a warm-up call has built the block lists) and replayed
+    with other work and synchronisations in between; every replay must reproduce the eager result
+    for whatever the input buffers hold at that moment."""
+    w = inp.WORKLOADS["ragged128"]
+    print("case graph", flush=True)
+    rl, ol = lay(w)
+    Q, K, V = inp.full_qkv(w, DEV, 6.0)
+    ws = torch.empty(rf.rf_attention_workspace_bytes(w.B, w.nH, w.D, rl, None), dtype=torch.uint8, device=DEV)
+    arm_ws = torch.empty(rf.rf_arm_workspace_bytes(w.B, w.nH, rl), dtype=torch.uint8, device=DEV)
+    hc = torch.empty(w.B, w.nH, dtype=torch.int32, device=DEV)
+    rec = torch.empty(w.B, w.nH, 2, dtype=torch.float32, device=DEV)
+    O = torch.empty_like(Q)
+
+    def step():
+        rf.rf_arm_classify(Q, K, rl, None, rf.RF_SAMPLE_FIRST_FRAME, 0.45, hc, rec, arm_ws)
+        rf.rf_sparse_attention(Q, K, V, hc, rl, None, 128, out=O, workspace=ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()  # warm-up: builds and uploads the lists, sets kernel attributes
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    torch.cuda.synchronize()
+    for trial, scale in enumerate((6.0, 1.0, 9.0)):
+        fresh = inp.full_qkv(w, DEV, scale)
+        for dst, src in zip((Q, K, V), fresh):
+            dst.copy_(src)
+        O.zero_()
+        hc.fill_(-7)
+        graph.replay()
+        torch.cuda.synchronize()
+        O_graph, hc_graph = O.clone(), hc.clone()
+        junk = (Q.float() @ K.float().transpose(-1, -2)).sum()  # unrelated eager work between replays
+        step()
+        torch.cuda.synchronize()
+        assert torch.equal(hc_graph, hc), trial
+        assert torch.equal(O_graph, O), (trial, float(junk))  # same kernels, same order of work per row
+        for b in range(w.B):
+            for h in range(w.nH):
+                q, k, v = (f32(t) for t in inp.head_qkv(w, b, h, scale))
+                check(O_graph[b, h], orc.attention(q, k, v, int(hc_graph[b, h]), ol), "graph replay %d head(%d,%d)" % (trial, b, h))
+
+
+def test_calls_on_two_streams_do_not_share_state():
+    """Two attention calls in flight at once on different streams (each with its own workspace) take
+    different work-queue counters; both must be right."""
+    w = inp.WORKLOADS["ragged96"]
+    print("case two streams", flush=True)
+    rl, ol = lay(w)
+    Q, K, V = inp.full_qkv(w, DEV, 6.0)
+    classes = [torch.full((w.B, w.nH), c, dtype=torch.int32, device=DEV) for c in (rf.RF_TEMPORAL, rf.RF_TEXTURAL)]
+    wss = [torch.empty(rf.rf_attention_workspace_bytes(w.B, w.nH, w.D, rl, None), dtype=torch.uint8, device=DEV) for _ in range(2)]
+    outs = [torch.empty_like(Q) for _ in range(2)]
+    rf.rf_sparse_attention(Q, K, V, classes[0], rl, None, 64, out=outs[0], workspace=wss[0])  # lists built
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(8):
+        for i, s in enumerate(streams):
+            with torch.cuda.stream(s):
+                rf.rf_sparse_attention(Q, K, V, classes[i], rl, None, 64, out=outs[i], workspace=wss[i])
+    torch.cuda.synchronize()
+    for i, cls in enumerate((rf.RF_TEMPORAL, rf.RF_TEXTURAL)):
+        for h in range(w.nH):
+            q, k, v = (f32(t) for t in inp.head_qkv(w, 0, h, 6.0))
+            check(outs[i][0, h], orc.attention(q, k, v, cls, ol), "stream %d head %d" % (i, h))
