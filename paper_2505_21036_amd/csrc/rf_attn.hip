@@ -652,9 +652,7 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xc
         const int e0 = pl.row_ptr[list][qk.qb];
         qk.ntiles = pl.row_ptr[list][qk.qb + 1] - e0;
         qk.cols = pl.cols[list] + e0;
-#ifndef RF_NO_ROTATE
         qk.first = pl.first_entry[list][qk.qb];
-#endif
         qk.keyN = pl.N;
         attend<D, NW, MODE_LISTED>(a, pl, qk, smem);
     }
