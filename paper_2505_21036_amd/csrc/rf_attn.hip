@@ -1,11 +1,12 @@
 // Block-sparse attention forward for RainFusion's head patterns (Eq. 1-5; Fig. 2a), gfx950.
 //
-// One workgroup = one query block (64 or 128 rows) of one head.  It reads the head's class on
-// the device, walks that class's list of 64-key tiles (skipped tiles cost no traffic), stages K
-// and V^T tiles through LDS with one tile of prefetch held in registers, forms the transposed
-// score tile with bf16 MFMA, runs the online softmax in fp32 with exp2, and accumulates
-// O^T = V^T P^T with bf16 MFMA.  In tiles flagged partial the token-level predicate of the
-// pattern is re-applied to each score.
+// Work item = one query block (64, 128 or 256 rows) of one head; a resident set of workgroups
+// takes items from per-XCD queues.  For its item a workgroup reads the head's class on the device,
+// walks that class's list of 64-key tiles (skipped tiles cost no traffic), loads K and V tiles
+// global -> LDS one tile ahead without staging registers, forms the transposed score tile with
+// bf16 MFMA, runs the online softmax in fp32 with exp2, and accumulates O^T = V^T P^T with bf16
+// MFMA.  In tiles flagged partial the token-level predicate of the pattern is re-applied to each
+// score.
 #include <algorithm>
 
 #include "rf_device.h"
@@ -194,13 +195,8 @@ struct DirectTile {
 };
 
 template <int D, int NW>
-struct TileFor {
-    using type = DirectTile<D, NW>;
-};
-
-template <int D, int NW>
 struct AttnSmem {
-    using ST = typename TileFor<D, NW>::type;
+    using ST = DirectTile<D, NW>;
     // K/V tiles resident at a time: the one being consumed plus AHEAD on their way
     static constexpr int AHEAD = RF_TILES_AHEAD;
     static constexpr int DEPTH = AHEAD + 1;
@@ -233,7 +229,7 @@ constexpr float kRescaleSlack = 8.f;
 template <int D, int NW, int MODE>
 __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, const QueryBlock& qk, unsigned char* smem) {
     constexpr int BQ = 32 * NW;
-    using ST = typename TileFor<D, NW>::type;
+    using ST = DirectTile<D, NW>;
     using SM = AttnSmem<D, NW>;
     constexpr int DEPTH = SM::DEPTH;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, m = lane & 31;
