@@ -188,9 +188,11 @@ int rf_plan_host(const rf_layout *layout, const rf_params *params, int block, in
 /*
  * Host-side view of how rf_sparse_attention schedules a head's query blocks under pattern `cls`
  * (scheduling only: it affects cache behaviour and load balance, never the result).
- *   order       : host, int32 [nQB], receives a permutation of 0..nQB-1: the order in which blocks are
- *                 handed out (identity for RF_DENSE); XCD x of the GPU runs entries
- *                 [x * ceil(nQB/8), (x+1) * ceil(nQB/8)) of it.
+ *   order       : host, int32 [nQB], receives a permutation of 0..nQB-1.  First the blocks that hold
+ *                 text rows (the long ones: text queries see every key): they are handed out, for all
+ *                 heads, before anything else.  Then the other nV blocks in a locality order (token
+ *                 order for RF_DENSE), of which XCD x of the GPU owns entries
+ *                 [x * ceil(nV/8), (x+1) * ceil(nV/8)), head after head.
  *   first_entry : host, int32 [nQB] or NULL: per query block, the entry of its rf_plan_host list at
  *                 which its walk starts (it wraps around), chosen so that blocks in flight together
  *                 on an XCD sweep the same key tiles at the same time; 0 where the list is not one

@@ -24,8 +24,7 @@ def compile_flags(extra_flags=()):
     # verifies on the generated assembly that nothing else in that file uses M0.
     return ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"),
             "-I", CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
-            "-Wno-unused-command-line-argument", "-Wno-inline-asm", "-DRF_SCHED_QK=4",
-            "-DRF_SCHED_PV=3"] + list(extra_flags)
+            "-Wno-unused-command-line-argument", "-Wno-inline-asm"] + list(extra_flags)
 
 
 def device_assembly(source, extra_flags=()):

@@ -412,7 +412,8 @@ int rf_plan_order(const rf_layout* layout, const rf_params* params, int block, i
     HostPlan hp;
     build_plan(g, block, &hp);
     const int list = cls == RF_LIST_TEMPORAL_POSITION_MAJOR ? kListTemporalPM : cls;
-    for (int i = 0; i < hp.nQB; ++i) order[i] = cls == RF_DENSE ? i : hp.qorder[list][i];
+    // dense heads: the same scheme with plain token order for the blocks without text rows
+    for (int i = 0; i < hp.nQB; ++i) order[i] = hp.qorder[cls == RF_DENSE ? RF_SPATIAL : list][i];
     if (first_entry)
         for (int i = 0; i < hp.nQB; ++i) first_entry[i] = cls == RF_DENSE ? 0 : hp.first_entry[list][i];
     return RF_OK;

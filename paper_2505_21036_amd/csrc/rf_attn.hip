@@ -94,7 +94,7 @@ struct DirectTile {
     int wave, lane;
     int k_base;          // byte offset of this lane's K operand for kb2 = 0 (chunk 0 of its row when !POW2)
     int k_rot;           // !POW2: hf + rotation of this lane's K row
-    int v_base[D / 32];  // byte offset of this lane's V operand for u = 0, first half, per channel block
+    int v_base;          // byte offset of this lane's V operand for u = 0, first half, channel block 0
     // Loads of a tile of consecutive tokens: load j of a lane reads  base + j*STEP + lane_off[j].
     // With power-of-two rows a lane keeps its slot position and moves down ROWS_PER_LOAD rows per
     // load, and the permutations have period 16 (K) and 4 (V) rows, so one offset serves every j
@@ -119,12 +119,12 @@ struct DirectTile {
             if (j < K_VARIANTS) k_lane_off[j] = row * ROW + 16 * k_chunk(row, pos) - j * STEP;
             if (j < V_VARIANTS) v_lane_off[j] = row * ROW + 16 * v_slot(row, pos) - j * STEP;
         }
-        const int vrow = 8 * hf + (i >> 2);  // + 16*u + 4*half: multiples of 4, invisible to the V permutation
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db) {
-            const int chunk = 4 * db + 2 * (g4 & 1) + ((i & 3) >> 1);
-            v_base[db] = vrow * ROW + 16 * v_slot(vrow, chunk) + 8 * (i & 1);
-        }
+        // V operand of channel block db: chunk 4*db + r of row vrow (+ 16*u + 4*half: multiples of 4,
+        // invisible to the V permutation).  With the XOR permutation the chunk lands in slot
+        // 4*(db ^ y) + r, i.e. at v_base ^ 64*db; unpermuted (head_dim 96) at v_base + 64*db.
+        const int vrow = 8 * hf + (i >> 2);
+        const int chunk0 = 2 * (g4 & 1) + ((i & 3) >> 1);
+        v_base = vrow * ROW + 16 * v_slot(vrow, chunk0) + 8 * (i & 1);
     }
 
     // tok(row): token whose K/V row goes to tile row `row`; kh/vh: byte pointers the tokens index
@@ -162,30 +162,36 @@ struct DirectTile {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LATER * MIN_LOADS_PER_TILE) : "memory");
     }
 
+    // Per-tile LDS addresses of this lane's operands.  Both are made opaque once per tile, so that what
+    // the loop carries is one K and one V register per lane rather than a hoisted register per
+    // (chunk, channel block): the tile buffers start at multiples of 256 bytes, so the XORs that
+    // select a chunk commute with adding the buffer's address.
+    __device__ __forceinline__ uint32_t k_address(const unsigned char* kl) const {
+        uint32_t ka = lds_offset(kl) + k_base;
+        asm volatile("" : "+v"(ka));
+        return ka;
+    }
+    __device__ __forceinline__ uint32_t v_address(const unsigned char* vl) const {
+        uint32_t va = lds_offset(vl) + v_base;
+        asm volatile("" : "+v"(va));
+        return va;
+    }
     // A operand of S^T = K Q^T: keys 32*kb2 .. +31 (permuted per lane), channels 16*c + 8*hf .. +7
-    __device__ __forceinline__ bf16x8 k_frag(const unsigned char* kl, int kb2, int c) const {
-        int off;
+    __device__ __forceinline__ bf16x8 k_frag(uint32_t ka, int kb2, int c) const {
+        typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+        uint32_t addr;
         if (POW2) {
-            off = k_base ^ (32 * c);  // chunk 2c + hf: the permutation is an XOR, so c toggles address bits
+            addr = ka ^ (32 * c);  // chunk 2c + hf: the permutation is an XOR, so c toggles address bits
         } else {
             const int p = 2 * c + k_rot;
-            off = k_base + 16 * (p >= CH ? p - CH : p);
+            addr = ka + 16 * (p >= CH ? p - CH : p);
         }
-        return as_bf16x8(*reinterpret_cast<const u32x4*>(kl + off + kb2 * 32 * ROW));
-    }
-    // LDS address of this lane's V operand for u = 0 in tile `vl`, per channel block.  Kept opaque so
-    // that the 32 reads of a tile are this address plus an immediate, not 32 separate address registers.
-    __device__ __forceinline__ void v_addresses(const unsigned char* vl, uint32_t (&va)[D / 32]) const {
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db) {
-            va[db] = lds_offset(vl) + v_base[db];
-            asm volatile("" : "+v"(va[db]));
-        }
+        return as_bf16x8(*(lds_u32x4*)(uintptr_t)(addr + kb2 * 32 * ROW));
     }
     // A operand of O^T = V^T P^T: channels 32*db + lane%32, keys 16*u + 8*hf .. +7
-    static __device__ __forceinline__ bf16x8 v_frag(uint32_t va, int u) {
+    static __device__ __forceinline__ bf16x8 v_frag(uint32_t va, int db, int u) {
         typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-        const uint32_t p = va + 16 * u * ROW;
+        const uint32_t p = (POW2 ? va ^ (64 * db) : va + 64 * db) + 16 * u * ROW;
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(p));
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(p + 4 * ROW));
         typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -204,7 +210,10 @@ struct AttnSmem {
     static constexpr int K_OFF = 0;
     static constexpr int V_OFF = DEPTH * ST::K_BYTES;
     static constexpr int SIDE_OFF = V_OFF + DEPTH * ST::V_BYTES;  // ring of 64-int slots: key indices or key attributes
-    static constexpr int BYTES = SIDE_OFF + SIDE_SLOTS * kTileK * 4;
+    static constexpr int ITEM_OFF = SIDE_OFF + SIDE_SLOTS * kTileK * 4;  // two ints: the work item just taken
+    static constexpr int BYTES = ITEM_OFF + 16;
+    static_assert(K_OFF % 256 == 0 && V_OFF % 256 == 0 && ST::K_BYTES % 256 == 0 && ST::V_BYTES % 256 == 0,
+                  "tile buffers must start at multiples of 256 bytes (see DirectTile::k_address)");
 };
 
 struct QueryBlock {
@@ -221,6 +230,16 @@ struct QueryBlock {
     int ntiles;           // key tiles to visit
     int keyN;             // length of the key sequence walked (N, or Nc when compacted)
 };
+
+// MFMA operand reads from LDS are issued this many MFMAs ahead of their use (K: one 16-byte read per
+// operand; V: two transposing 8-byte reads per operand).
+#ifndef RF_AHEAD_K
+#define RF_AHEAD_K 4
+#endif
+#ifndef RF_AHEAD_V
+#define RF_AHEAD_V 3
+#endif
+constexpr int kAheadK = RF_AHEAD_K, kAheadV = RF_AHEAD_V;
 
 // exp2 arguments may exceed 0 by at most this much before the running reference is moved: the
 // softmax is invariant to the reference, so a stale one only costs range, which fp32/bf16 have.
@@ -328,25 +347,22 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
 
     // S^T of tile t (64 keys x this lane's query), predicate applied where the tile is partial
     auto scores = [&](int t, int entry, f32x16 (&s)[2]) {
-        const unsigned char* kl = k_lds(t);
-        // the two 32-key halves are independent accumulation chains: alternate them
+        const uint32_t ka = st.k_address(k_lds(t));
+        // The two 32-key halves are independent accumulation chains: alternate them.  Operand reads run
+        // kAheadK MFMAs ahead of their use; the fences keep the compiler's scheduler from undoing that
+        // order (left to itself it sometimes issues read, wait, MFMA, read, wait, ...).
+        constexpr int NQK = 2 * (D / 16);
+        bf16x8 frag[NQK];
+#pragma unroll
+        for (int i = 0; i < kAheadK; ++i) frag[i] = st.k_frag(ka, i & 1, i >> 1);
         s[0] = f32x16{0};
         s[1] = f32x16{0};
 #pragma unroll
-        for (int cc = 0; cc < D / 16; ++cc)
-#pragma unroll
-            for (int kb2 = 0; kb2 < 2; ++kb2)
-                s[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st.k_frag(kl, kb2, cc), qf[cc], s[kb2], 0, 0, 0);
-#ifdef RF_SCHED_QK
-        // keep RF_SCHED_QK operand reads in flight ahead of the MFMA that consumes them
-        __builtin_amdgcn_sched_group_barrier(0x100, RF_SCHED_QK, 0);
-#pragma unroll
-        for (int i = 0; i < 2 * (D / 16) - RF_SCHED_QK; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        for (int j = 0; j < NQK; ++j) {
+            if (j + kAheadK < NQK) frag[j + kAheadK] = st.k_frag(ka, (j + kAheadK) & 1, (j + kAheadK) >> 1);
+            s[j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[j], qf[j >> 1], s[j & 1], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, RF_SCHED_QK, 0);
-#endif
         if (entry & RF_PLAN_PARTIAL) {
             const int k0 = (entry & kTileIndexMask) * kTileK;
             const int* al = side + (t % SM::SIDE_SLOTS) * kTileK;
@@ -388,26 +404,19 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
     // O^T += V^T P^T for tile t, P (bf16) in pf
     bf16x8 pf[4];
     auto accumulate = [&](int t) {
-        uint32_t va[D / 32];
-        st.v_addresses(v_lds(t), va);
-        // consecutive MFMAs go to different accumulators (channel blocks): no back-to-back dependence
+        const uint32_t va = st.v_address(v_lds(t));
+        // consecutive MFMAs go to different accumulators (channel blocks): no back-to-back dependence;
+        // operand reads kAheadV MFMAs ahead, order fenced as for the scores
+        constexpr int NPV = 4 * (D / 32), NDB = D / 32;
+        bf16x8 frag[NPV];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int i = 0; i < kAheadV; ++i) frag[i] = ST::v_frag(va, i % NDB, i / NDB);
 #pragma unroll
-            for (int db = 0; db < D / 32; ++db)
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ST::v_frag(va[db], u), pf[u], oacc[db], 0, 0, 0);
-#ifdef RF_SCHED_PV
-        {
-            constexpr int PER = ST::V_READS_PER_FRAG, TOTAL = 4 * (D / 32);
-            __builtin_amdgcn_sched_group_barrier(0x100, RF_SCHED_PV * PER, 1);
-#pragma unroll
-            for (int i = 0; i < TOTAL - RF_SCHED_PV; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-                __builtin_amdgcn_sched_group_barrier(0x100, PER, 1);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, RF_SCHED_PV, 1);
+        for (int j = 0; j < NPV; ++j) {
+            if (j + kAheadV < NPV) frag[j + kAheadV] = ST::v_frag(va, (j + kAheadV) % NDB, (j + kAheadV) / NDB);
+            oacc[j % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[j], pf[j / NDB], oacc[j % NDB], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-#endif
     };
     // Software pipeline.  While tile t is consumed, the loads of tiles t+1 .. t+AHEAD are in flight
     // or landed, and the side data of tile t+DEPTH is on its way to its ring slot (one tile further,
@@ -520,27 +529,35 @@ extern "C" int rf_debug_set_trace(void* p) { return static_cast<int>(hipMemcpyTo
 // blocks (measured best; its accumulators are half the size), two otherwise.
 constexpr int attn_waves_per_simd(int D, int NW) { return (D == 64 && NW == 4) ? 3 : 2; }  // NW = 8: one workgroup per CU
 
-// The next (head, query block) item for a workgroup whose home queue is `home`, or -1 when every
-// queue is empty.  Queue x holds, head after head, the ordinals [x * per_xcd, (x+1) * per_xcd) of
-// the block order; ctr[x] counts how many of its items have been handed out.  A workgroup drains its
-// home queue first (its neighbours on the XCD are on the same part of the same head, which is what
-// the L2 wants) and then helps whichever queue has the most left.  Every path ends: counters only
-// grow, a failed take means another workgroup took that item, and once all are taken -1 is returned.
-__device__ __forceinline__ int take_item(int* ctr, int home, int BH, int nQB, int per_xcd, int* queue) {
-    auto items = [&](int x) { return max(0, min(per_xcd, nQB - x * per_xcd)) * BH; };
+// Items of one launch.  Queue x holds first its share of the long items (the nTB text-holding blocks
+// of every head: global index i = head * nTB + k goes to queue i mod 8), then, head after head, the
+// ordinals [x * per_xcd, (x+1) * per_xcd) of the order of the nVB other blocks.
+struct Queues {
+    int BH, nVB, nTB, per_xcd;
+    __device__ __forceinline__ int long_items(int x) const { return (nTB * BH - x + 7) >> 3; }
+    __device__ __forceinline__ int share(int x) const { return max(0, min(per_xcd, nVB - x * per_xcd)); }
+    __device__ __forceinline__ int items(int x) const { return long_items(x) + share(x) * BH; }
+};
+
+// The next item for a workgroup whose home queue is `home`, or -1 when every queue is empty.
+// ctr[x] counts how many items of queue x have been handed out.  A workgroup drains its home queue
+// first (its neighbours on the XCD are on the same part of the same head, which is what the L2
+// wants) and then helps whichever queue has the most left.  Every path ends: counters only grow, a
+// failed take means another workgroup took that item, and once all are taken -1 is returned.
+__device__ __forceinline__ int take_item(int* ctr, int home, const Queues& qs, int* queue) {
     auto taken = [&](int x) { return __hip_atomic_load(ctr + x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
     int q = home;
     for (;;) {
-        if (taken(q) < items(q)) {
+        if (taken(q) < qs.items(q)) {
             const int j = __hip_atomic_fetch_add(ctr + q, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (j < items(q)) {
+            if (j < qs.items(q)) {
                 *queue = q;
                 return j;
             }
         }
         int best = -1, best_left = 0;
         for (int x = 0; x < 8; ++x) {
-            const int left = items(x) - taken(x);
+            const int left = qs.items(x) - taken(x);
             if (left > best_left) {
                 best_left = left;
                 best = x;
@@ -552,7 +569,7 @@ __device__ __forceinline__ int take_item(int* ctr, int home, int BH, int nQB, in
 }
 
 template <int D, int NW>
-__device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xcd, int nQB, int per_xcd, unsigned char* smem);
+__device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xcd, const Queues& qs, unsigned char* smem);
 
 __global__ void reset_queue_kernel(int* ctr) {
     if (threadIdx.x < 8) ctr[threadIdx.x] = 0;
@@ -560,8 +577,8 @@ __global__ void reset_queue_kernel(int* ctr) {
 
 template <int D, int NW>
 __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(attn_waves_per_simd(D, NW), attn_waves_per_simd(D, NW)))) attn_kernel(AttnArgs a) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    __shared__ int item_box[2];
+    extern __shared__ __attribute__((aligned(256))) unsigned char smem[];  // the kernel's only LDS: starts at address 0
+    int* item_box = reinterpret_cast<int*>(smem + AttnSmem<D, NW>::ITEM_OFF);
     // A resident set of workgroups (as many as fit on the chip) works through the (head, query
     // block) items.  Workgroup ids go to the 8 XCDs round-robin; XCD x's queue is one eighth of every
     // head's block order, head after head (neighbours in that order walk nearly the same key tiles,
@@ -569,11 +586,15 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
     // K/V of the head in flight (tens of MB) stays resident in the memory-side cache for whatever
     // misses L2.  XCDs differ in speed by several per cent and shares in work; an XCD whose queue is
     // empty takes items from the others.
-    const int nQB = a.plan[0].nQB, per_xcd = (nQB + 7) >> 3;
+    Queues qs;
+    qs.BH = a.BH;
+    qs.nVB = a.plan[0].first_text_qb;
+    qs.nTB = a.plan[0].nQB - qs.nVB;
+    qs.per_xcd = (qs.nVB + 7) >> 3;
     for (;;) {
         if (threadIdx.x == 0) {
             int q = 0;
-            item_box[0] = take_item(a.queue, blockIdx.x & 7, a.BH, nQB, per_xcd, &q);
+            item_box[0] = take_item(a.queue, blockIdx.x & 7, qs, &q);
             item_box[1] = q;
         }
         __syncthreads();
@@ -581,20 +602,30 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
         const int item = __builtin_amdgcn_readfirstlane(item_box[0]), xcd = __builtin_amdgcn_readfirstlane(item_box[1]);
         __syncthreads();
         if (item < 0) break;
-        process_item<D, NW>(a, item, xcd, nQB, per_xcd, smem);
+        process_item<D, NW>(a, item, xcd, qs, smem);
     }
 }
 
 // One (head, query block) item: item-th of queue xcd.
 template <int D, int NW>
-__device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xcd, int nQB, int per_xcd, unsigned char* smem) {
-    const int share = max(0, min(per_xcd, nQB - xcd * per_xcd));
-    const int ordinal = xcd * per_xcd + item % share;
+__device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xcd, const Queues& qs, unsigned char* smem) {
+    // position in the block order, and the head
+    int ordinal, bh;
+    const int longs = qs.long_items(xcd);
+    if (item < longs) {
+        const int i = item * 8 + xcd;
+        bh = i / qs.nTB;
+        ordinal = i % qs.nTB;
+    } else {
+        const int share = qs.share(xcd), j = item - longs;
+        bh = j / share;
+        ordinal = qs.nTB + xcd * qs.per_xcd + j % share;
+    }
 #ifdef RF_TRACE
     const unsigned long long trace_t0 = wall_clock64();
 #endif
     QueryBlock qk;
-    qk.bh = item / share;
+    qk.bh = bh;
     // per-head bandwidth: the plans differ only in the Spatial / Temporal lists, radii and block order
     int which = 0;
     if (a.head_bw) {
@@ -608,7 +639,8 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xc
     // a Temporal head walks the position-major copy of its K and V if the caller gave room for one
     const bool temporal_pm = cls == RF_TEMPORAL && a.packed_k;
     const int list = temporal_pm ? kListTemporalPM : cls;
-    qk.qb = cls == RF_DENSE ? ordinal : pl.qorder[list][ordinal];
+    // dense heads: text-holding blocks first, then token order
+    qk.qb = cls == RF_DENSE ? (ordinal < qs.nTB ? qs.nVB + ordinal : ordinal - qs.nTB) : pl.qorder[list][ordinal];
     qk.first = 0;
     qk.cols = nullptr;
     qk.list = cls;
@@ -654,7 +686,7 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xc
     }
 #ifdef RF_TRACE
     if (g_trace && threadIdx.x == 0) {
-        unsigned long long* rec = g_trace + 4 * (static_cast<size_t>(qk.bh) * nQB + ordinal);
+        unsigned long long* rec = g_trace + 4 * (static_cast<size_t>(qk.bh) * (qs.nVB + qs.nTB) + ordinal);
         rec[0] = trace_t0;
         rec[1] = wall_clock64();
         rec[2] = (static_cast<unsigned long long>(blockIdx.x) << 32) | static_cast<unsigned>(qk.ntiles);

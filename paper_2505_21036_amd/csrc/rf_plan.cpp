@@ -66,55 +66,50 @@ inline int span_reach(Span a, Span b) { return std::max(b.hi - a.lo, a.hi - b.lo
 }  // namespace
 
 // How a head's query blocks are handed to workgroups.  The attention kernel runs one queue of
-// (head, query block) items per XCD (each XCD has its own L2): XCD x owns the ordinals
-// [x * ceil(nQB/8), (x+1) * ceil(nQB/8)) of the order built here, head after head, and takes items
-// from other XCDs' queues once its own is empty, so the shares need not hold equal work.  What the
-// order must provide is locality: blocks that run together (an XCD has about kConcurrentRows query
-// rows in flight, a generation) should walk the same key tiles at the same time, so that a tile is
-// fetched into the XCD's L2 once.  Hence:
-//  - token order; under the Temporal pattern in token order, whose lists depend only on the
-//    in-frame position, blocks are grouped by position across frames; under the Textural pattern
-//    the blocks with text rows (the only ones that differ) come first;
-//  - in the banded lists (Spatial; Temporal in position-major order) a block's tiles are one
-//    contiguous range that slides with the block, so the blocks of a generation all start their
-//    walk at the same tile, the first tile of the generation's last block, and wrap around: they
-//    then sweep the same tiles in step instead of each trailing its neighbour by the slide.
+// (head, query block) items per XCD (each XCD has its own L2) and a workgroup takes items from other
+// XCDs' queues once its own is empty, so the queues need not hold equal work.  Two things matter:
+//  - The blocks that hold text rows are the long items (text queries see every key, so such a block
+//    walks the whole sequence under every pattern).  They come first in the order, and the kernel
+//    hands them out, for all heads, before anything else: the launch must not end waiting for one.
+//  - The other blocks follow in a locality order, of which XCD x owns the x-th eighth, head after
+//    head: blocks that run together (an XCD has about kConcurrentRows query rows in flight, a
+//    generation) should walk the same key tiles at the same time, so that a tile is fetched into
+//    the XCD's L2 once.  That order is token order (under the Temporal pattern in token order,
+//    whose lists depend only on the in-frame position: grouped by position across frames); and in
+//    the banded lists (Spatial; Temporal in position-major order), where a block's tiles are one
+//    contiguous range that slides with the block, the blocks of a generation all start their walk
+//    at the same tile, the first tile of the generation's last block, and wrap around: they then
+//    sweep the same tiles in step instead of each trailing its neighbour by the slide.
 static void order_query_blocks(HostPlan* plan) {
     HostPlan& P = *plan;
-    const int nQB = P.nQB, block = P.block, HW = P.g.HW, Nv = P.g.Nv;
-    const int per_share = (nQB + 7) / 8;
+    const int nQB = P.nQB, block = P.block, HW = P.g.HW;
+    const int nVB = P.first_text_qb, nTB = nQB - nVB;  // video-only blocks, text-holding blocks
+    const int per_share = (nVB + 7) / 8;
     constexpr int kConcurrentRows = 8192;  // 32 CUs x 256 rows
     const int generation = std::max(1, kConcurrentRows / block);
     for (int cls = 0; cls < kLists; ++cls) {
         std::vector<int32_t>& ord = P.qorder[cls];
         ord.resize(nQB);
-        for (int qb = 0; qb < nQB; ++qb) ord[qb] = qb;
+        for (int i = 0; i < nTB; ++i) ord[i] = nVB + i;
+        for (int qb = 0; qb < nVB; ++qb) ord[nTB + qb] = qb;
         if (cls == RF_TEMPORAL) {
-            auto key = [&](int qb) {
-                const int64_t q0 = static_cast<int64_t>(qb) * block;
-                return q0 < Nv ? (q0 % HW) / block : (HW / block + 1);  // blocks that start in the text go last
-            };
-            std::stable_sort(ord.begin(), ord.end(), [&](int a, int b) { return key(a) < key(b); });
-        }
-        if (cls == RF_TEXTURAL) {
-            // the few blocks that hold text rows walk the whole sequence, twice the work of the others:
-            // hand them out first, so that they are not what the end of the launch waits for
-            std::stable_partition(ord.begin(), ord.end(), [&](int qb) { return qb >= P.first_text_qb; });
+            auto key = [&](int qb) { return (static_cast<int64_t>(qb) * block % HW) / block; };
+            std::stable_sort(ord.begin() + nTB, ord.end(), [&](int a, int b) { return key(a) < key(b); });
         }
         std::vector<int32_t>& fe = P.first_entry[cls];
         fe.assign(nQB, 0);
         if (cls != RF_SPATIAL && cls != kListTemporalPM) continue;
         auto tile_of = [&](int e) { return P.cols[cls][e] & kTileIndexMask; };
-        for (int s0 = 0; s0 < nQB; s0 += per_share)
-            for (int g0 = s0; g0 < std::min(s0 + per_share, nQB); g0 += generation) {
-                const int g1 = std::min({g0 + generation, s0 + per_share, nQB});
+        for (int s0 = 0; s0 < nVB; s0 += per_share)
+            for (int g0 = s0; g0 < std::min(s0 + per_share, nVB); g0 += generation) {
+                const int g1 = std::min({g0 + generation, s0 + per_share, nVB});
                 int start_tile = 0;
                 for (int o = g0; o < g1; ++o) {
-                    const int qb = ord[o];
+                    const int qb = ord[nTB + o];
                     if (P.row_ptr[cls][qb] < P.row_ptr[cls][qb + 1]) start_tile = std::max(start_tile, tile_of(P.row_ptr[cls][qb]));
                 }
                 for (int o = g0; o < g1; ++o) {
-                    const int qb = ord[o], e0 = P.row_ptr[cls][qb], e1 = P.row_ptr[cls][qb + 1];
+                    const int qb = ord[nTB + o], e0 = P.row_ptr[cls][qb], e1 = P.row_ptr[cls][qb + 1];
                     int e = e0;
                     while (e < e1 && tile_of(e) < start_tile) ++e;
                     fe[qb] = e < e1 ? e - e0 : 0;

@@ -24,3 +24,36 @@ def test_m0_is_used_only_by_the_tile_loads():
     assert loads > 0
     # every explicit wait of the pipeline is still there: one vmcnt wait per tile-loop barrier at least
     assert sum("s_waitcnt vmcnt(0)" in l for l in code) >= 4
+
+
+def _tile_loops(asm, kernel):
+    """Instruction lists of the innermost loops of `kernel` that hold one tile's 32 MFMAs."""
+    lines = asm.splitlines()
+    start = next(i for i, l in enumerate(lines) if l.startswith(kernel + ":"))
+    end = next(i for i in range(start, len(lines)) if "s_endpgm" in lines[i])
+    lines = lines[start:end]
+    label_at = {m.group(1): i for i, l in enumerate(lines) for m in [re.match(r"^(\.LBB\d+_\d+):", l)] if m}
+    loops = []
+    for i, l in enumerate(lines):
+        m = re.search(r"s_c?branch\w*\s+(\.LBB\d+_\d+)", l)
+        if m and label_at.get(m.group(1), len(lines)) < i:
+            body = [x.strip() for x in lines[label_at[m.group(1)]:i + 1]]
+            body = [x for x in body if x and not x.startswith((";", "."))]
+            if sum(x.startswith("v_mfma") for x in body) == 32:
+                loops.append(body)
+    return loops
+
+
+def test_tile_loops_keep_operand_reads_ahead_of_the_mfmas():
+    """Performance guard on the generated code of the headline kernel (head_dim 128, 256-row blocks):
+    in every tile loop the LDS operand reads run ahead of the MFMAs that use them, which shows as
+    waits for all-but-3 / all-but-4 outstanding LDS operations.  (A schedule that reads, waits for
+    everything and then issues one MFMA costs ~9 % and has appeared from unrelated edits.)"""
+    asm = device_assembly("rf_attn.hip")
+    loops = _tile_loops(asm, "_ZN2rf11attn_kernelILi128ELi8EEEvNS_8AttnArgsE")
+    assert len(loops) >= 3  # every-tile walk (dense / packed), compacted walk, listed walk
+    for body in loops:
+        waits = [x for x in body if x.startswith("s_waitcnt") and "lgkmcnt" in x]
+        ahead = sum("lgkmcnt(3)" in x or "lgkmcnt(4)" in x for x in waits)
+        assert ahead >= 24, (ahead, len(waits))
+        assert not any(x.startswith("scratch_") for x in body)  # no spills inside a tile loop

@@ -155,44 +155,47 @@ def test_query_block_order_is_a_permutation(lay, block):
     for cls in (rf.RF_SPATIAL, rf.RF_TEMPORAL, rf.RF_TEXTURAL, rf.RF_DENSE):
         order = rf.rf_plan_order(rl, None, block, cls)
         assert sorted(order.tolist()) == list(range(nqb))
-    assert (rf.rf_plan_order(rl, None, block, rf.RF_DENSE) == np.arange(nqb)).all()
+    n_video = lay[0] * lay[1] * lay[2] // block if lay[3] else nqb  # blocks without text rows
+    want = np.r_[np.arange(n_video, nqb), np.arange(n_video)]       # text-holding blocks first, then token order
+    assert (rf.rf_plan_order(rl, None, block, rf.RF_DENSE) == want).all()
 
 
 def test_query_block_order_keeps_neighbours_together():
-    """The XCD queues are eighths of the order; blocks next to each other in it must be neighbours in
-    the sequence (token order, or position-grouped for Temporal in token order)."""
+    """Text-holding blocks (the long items) lead the order; the XCD queues are eighths of the rest, where
+    blocks next to each other must be neighbours in the sequence (token order, or position-grouped for
+    Temporal in token order)."""
     rl = rf.rf_layout(33, 45, 80, 256)
     for block in (128, 256):
-        for cls in (rf.RF_SPATIAL, rf.RF_TEXTURAL, rf.RF_DENSE, rf.RF_LIST_TEMPORAL_POSITION_MAJOR):
+        n_video = 33 * 45 * 80 // block
+        for cls in (rf.RF_SPATIAL, rf.RF_TEXTURAL, rf.RF_DENSE, rf.RF_LIST_TEMPORAL_POSITION_MAJOR, rf.RF_TEMPORAL):
             order, first = rf.rf_plan_order(rl, None, block, cls, full=True)
-            if cls == rf.RF_TEXTURAL:  # blocks holding text rows (twice the work) first, then token order
-                n_text = len(order) - 33 * 45 * 80 // block
-                assert (order[:n_text] == np.arange(len(order) - n_text, len(order))).all()
-                assert (order[n_text:] == np.arange(len(order) - n_text)).all()
+            n_text = len(order) - n_video
+            assert n_text >= 1 and (order[:n_text] == np.arange(n_video, len(order))).all()
+            if cls != rf.RF_TEMPORAL:
+                assert (order[n_text:] == np.arange(n_video)).all()
             else:
-                assert (order == np.arange(len(order))).all()
+                pos = (order[n_text:].astype(np.int64) * block) % (45 * 80) // block
+                assert (np.diff(pos) >= 0).all()  # grouped by in-frame position
             work = np.diff(rf.rf_plan_host(rl, None, block, cls)[0])
             assert ((first >= 0) & (first < np.maximum(work, 1))).all()
-        order = rf.rf_plan_order(rl, None, block, rf.RF_TEMPORAL)
-        pos = (order.astype(np.int64) * block) % (45 * 80) // block
-        video = order.astype(np.int64) * block < 33 * 45 * 80
-        assert (np.diff(pos[video]) >= 0).all() and video[:video.sum()].all()  # grouped by in-frame position, text last
 
 
 @pytest.mark.parametrize("lay", [(7, 10, 13, 50), (33, 45, 80, 256)])
 def test_blocks_of_a_generation_start_at_a_common_tile(lay):
     """Banded lists: the blocks an XCD runs together (32 blocks of 256 rows out of its eighth of the
-    order) begin their cyclic walk at the same key tile wherever their lists hold it."""
+    text-free part of the order) begin their cyclic walk at the same key tile wherever their lists hold it."""
     rl = rf.rf_layout(*lay)
     block = 256
+    n_video = lay[0] * lay[1] * lay[2] // block
     for cls in (rf.RF_SPATIAL, rf.RF_LIST_TEMPORAL_POSITION_MAJOR):
         row_ptr, cols = rf.rf_plan_host(rl, None, block, cls)
         order, first = rf.rf_plan_order(rl, None, block, cls, full=True)
         tiles = cols & ~rf.RF_PLAN_PARTIAL
-        per = -(-len(order) // 8)
-        for s0 in range(0, len(order), per):
-            for g0 in range(s0, min(s0 + per, len(order)), 32):
-                blocks = order[g0:min(g0 + 32, s0 + per, len(order))]
+        rest = order[len(order) - n_video:]
+        per = -(-n_video // 8)
+        for s0 in range(0, n_video, per):
+            for g0 in range(s0, min(s0 + per, n_video), 32):
+                blocks = rest[g0:min(g0 + 32, s0 + per, n_video)]
                 lo = max(tiles[row_ptr[b]] for b in blocks)
                 for b in blocks:
                     mine = tiles[row_ptr[b]:row_ptr[b + 1]]
