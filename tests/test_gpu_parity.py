@@ -440,3 +440,21 @@ def test_calls_on_two_streams_do_not_share_state():
         for h in range(w.nH):
             q, k, v = (f32(t) for t in inp.head_qkv(w, 0, h, 6.0))
             check(outs[i][0, h], orc.attention(q, k, v, cls, ol), "stream %d head %d" % (i, h))
+
+
+@pytest.mark.parametrize("shape", [(3, 5, 64, 3, 7, 9, 33), (1, 7, 96, 9, 8, 8, 0), (2, 9, 128, 2, 16, 17, 300), (5, 1, 64, 11, 5, 5, 7)])
+def test_odd_batch_and_head_counts_through_the_queues(shape):
+    """Head counts that are not multiples of 8, fewer query blocks than XCDs, more text than video:
+    every (head, block) item must be processed exactly once whatever the queue shapes are."""
+    B, nH, D, T, H, W, tl = shape
+    print("case queues", shape, flush=True)
+    w = inp.Workload("odd", B, nH, D, T, H, W, tl, 64, 3000 + B * 17 + nH)
+    _, ol = lay(w)
+    Q, K, V = inp.full_qkv(w, DEV, 5.0)
+    classes = [(b * nH + h) % 4 for b in range(B) for h in range(nH)]
+    for block, packed in ((64, False), (128, True), (256, True)):
+        O = run_attention(w, Q, K, V, classes, block, packed=packed)
+        for b in range(B):
+            for h in range(nH):
+                q, k, v = (f32(t) for t in inp.head_qkv(w, b, h, 5.0))
+                check(O[b, h], orc.attention(q, k, v, classes[b * nH + h], ol), "odd %s blk%d head(%d,%d)" % (shape, block, b, h))
