@@ -458,3 +458,70 @@ def test_odd_batch_and_head_counts_through_the_queues(shape):
             for h in range(nH):
                 q, k, v = (f32(t) for t in inp.head_qkv(w, b, h, 5.0))
                 check(O[b, h], orc.attention(q, k, v, classes[b * nH + h], ol), "odd %s blk%d head(%d,%d)" % (shape, block, b, h))
+
+
+def test_random_small_configurations():
+    """Seeded sweep over layouts, parameters, flags, blocks and class mixes that the hand-picked cases
+    do not name: every head of every configuration against the oracle."""
+    rng = np.random.default_rng(20250521)
+    for case in range(28):
+        T, H, W = int(rng.integers(1, 9)), int(rng.integers(1, 13)), int(rng.integers(1, 13))
+        tl = int(rng.choice([0, 0, 1, 17, 64, 100, 200]))
+        D = int(rng.choice([64, 96, 128]))
+        B, nH = int(rng.integers(1, 3)), int(rng.integers(1, 6))
+        bs, bt = float(rng.choice([0.0, 0.07, 0.25, 0.5, 1.0])), float(rng.choice([0.0, 0.03, 0.25, 0.6, 1.0]))
+        tau = int(rng.integers(1, 6))
+        block = int(rng.choice([64, 128, 256]))
+        packed, text_first = bool(rng.integers(0, 2)), bool(rng.integers(0, 2)) and tl > 0
+        scale = float(rng.choice([1.0, 4.0, 10.0]))
+        w = inp.Workload("rand%d" % case, B, nH, D, T, H, W, tl, block, 5000 + case)
+        print("case random", case, (B, nH, D, T, H, W, tl), (bs, bt, tau), block, packed, text_first, scale, flush=True)
+        rl, ol = lay(w)
+        rp = rf.rf_params(bs, bt, tau, 0, rf.RF_FLAG_TEXT_FIRST if text_first else 0)
+        op = orc.Params(bs, bt, tau, 0, False, text_first)
+        shift = tl if text_first else 0
+        Q, K, V = (torch.roll(t, shift, dims=2).contiguous() for t in inp.full_qkv(w, DEV, scale))
+        classes = [int(c) for c in rng.integers(0, 4, size=B * nH)]
+        O = run_attention(w, Q, K, V, classes, block, rp, packed)
+        for b in range(B):
+            for h in range(nH):
+                q, k, v = (np.roll(f32(t), shift, axis=0) for t in inp.head_qkv(w, b, h, scale))
+                check(O[b, h], orc.attention(q, k, v, classes[b * nH + h], ol, op),
+                      "random %d head(%d,%d) cls%d" % (case, b, h, classes[b * nH + h]))
+
+
+def test_random_small_arm_configurations():
+    """Seeded sweep of the ARM: layouts, bandwidths, sampling intervals and modes, text in front or behind,
+    one or several candidate bandwidths; recalls within 1e-3 of the oracle, classes exact away from the threshold."""
+    rng = np.random.default_rng(60521)
+    for case in range(16):
+        T, H, W = int(rng.integers(1, 9)), int(rng.integers(2, 13)), int(rng.integers(2, 13))
+        tl = int(rng.choice([0, 5, 64, 130]))
+        D = int(rng.choice([64, 96, 128]))
+        B, nH = 1, int(rng.integers(1, 5))
+        bs, bt = float(rng.choice([0.0, 0.1, 0.25, 0.5])), float(rng.choice([0.0, 0.05, 0.25, 0.5]))
+        omega = int(rng.choice([0, 1, 2, 3, 7]))
+        mode = int(rng.integers(0, 2))
+        alpha = float(rng.choice([0.3, 0.5, 0.7]))
+        text_first = bool(rng.integers(0, 2)) and tl > 0
+        w = inp.Workload("rarm%d" % case, B, nH, D, T, H, W, tl, 64, 7000 + case)
+        print("case random arm", case, (nH, D, T, H, W, tl), (bs, bt, omega), mode, alpha, text_first, flush=True)
+        rl, ol = lay(w)
+        rp = rf.rf_params(bs, bt, 2, omega, rf.RF_FLAG_TEXT_FIRST if text_first else 0)
+        op = orc.Params(bs, bt, 2, omega, False, text_first)
+        shift = tl if text_first else 0
+        Q, K, _ = (torch.roll(t, shift, dims=2).contiguous() for t in inp.full_qkv(w, DEV, 3.0))
+        hc, rec = rf.rf_arm_classify(Q, K, rl, rp, mode, alpha)
+        hc, rec = hc.cpu().numpy(), rec.cpu().numpy()
+        bws = [0.5, 0.125, 0.25]
+        hcp, hbw, recp = (t.cpu().numpy() for t in rf.rf_arm_classify_plus(Q, K, rl, rp, mode, alpha, bws))
+        for h in range(nH):
+            q, k, _ = (np.roll(f32(t), shift, axis=0) for t in inp.head_qkv(w, 0, h, 3.0))
+            c, (rh, rt) = orc.arm_classify(q, k, ol, op, mode, alpha)
+            assert abs(rec[0, h, 0] - rh) <= 1e-3 and abs(rec[0, h, 1] - rt) <= 1e-3, (case, h, rec[0, h], rh, rt)
+            if min(abs(rh - alpha), abs(rt - alpha)) >= 1e-3:
+                assert hc[0, h] == c, (case, h, hc[0, h], c, rh, rt)
+            cp, idx, orec = orc.arm_classify_plus(q, k, ol, op, mode, alpha, bws)
+            assert np.abs(recp[0, h] - orec).max() <= 1e-3, (case, h, recp[0, h], orec)
+            if np.abs(orec - alpha).min() >= 1e-3:
+                assert (hcp[0, h], hbw[0, h]) == (cp, idx), (case, h, hcp[0, h], hbw[0, h], cp, idx)
