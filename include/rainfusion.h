@@ -16,7 +16,9 @@
  *     (layout, params, block) builds and uploads its block lists synchronously.  After
  *     such a warm-up call a sequence of calls only launches kernels (no memsets, no
  *     allocations) and can be captured into a HIP graph; results are bitwise the same
- *     from call to call.
+ *     from call to call.  Each rf_sparse_attention call takes the next of 64 small
+ *     library-owned counter sets per device (its work queues), so at most 64 attention
+ *     calls, or replays of captured ones, may be in flight on a device at a time.
  *   - Return value: RF_OK or a negative rf_status.  Arguments are validated before
  *     any GPU work, so a bad argument never launches a kernel.
  *   - `params == NULL` selects the paper's defaults (Sec. 4.1: both bandwidths 1/4,
