@@ -25,6 +25,9 @@ struct CachedPlan {
     const int32_t* local_pos = nullptr;   // [HW]   in-frame position of first-frame sample a
     const int32_t* global_pos = nullptr;  // [nG]   in-frame position of equal-interval sample a
     const int32_t* global_frame = nullptr;  // [nG] frame of equal-interval sample a
+    const int32_t* local_pos_range = nullptr;  // per 64-sample tile of each table: {min, max}
+    const int32_t* global_pos_range = nullptr;
+    const int32_t* global_frame_range = nullptr;
     int nG = 0;
 };
 
@@ -127,8 +130,18 @@ int get_arm_tables(const Geometry& g, const CachedPlan** out) {
             gp[a] = static_cast<int32_t>(tok % g.HW);
             gf[a] = static_cast<int32_t>(tok / g.HW);
         }
+        auto tile_ranges = [](const std::vector<int32_t>& v) {
+            std::vector<int32_t> r;
+            for (size_t t0 = 0; t0 < v.size(); t0 += kTileK) {
+                const size_t t1 = std::min(v.size(), t0 + kTileK);
+                r.push_back(*std::min_element(v.begin() + t0, v.begin() + t1));
+                r.push_back(*std::max_element(v.begin() + t0, v.begin() + t1));
+            }
+            return r;
+        };
         BlobBuilder bb;
         const size_t o0 = bb.add(lp), o1 = bb.add(gp), o2 = bb.add(gf);
+        const size_t r0 = bb.add(tile_ranges(lp)), r1 = bb.add(tile_ranges(gp)), r2 = bb.add(tile_ranges(gf));
         auto p = std::make_unique<CachedPlan>();
         p->g = g;
         p->block = 0;
@@ -139,6 +152,9 @@ int get_arm_tables(const Geometry& g, const CachedPlan** out) {
         p->local_pos = base + o0;
         p->global_pos = base + o1;
         p->global_frame = base + o2;
+        p->local_pos_range = base + r0;
+        p->global_pos_range = base + r1;
+        p->global_frame_range = base + r2;
         p->nG = nG;
         cp = p.get();
         g_plans.push_back(std::move(p));
@@ -274,9 +290,9 @@ static int arm_classify_impl(const void* Q, const void* K, int B, int nH, int D,
     a.N = g.N;
     a.first_video_row = g.video_shift();
     a.scale_log2 = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(D)));
-    if (sample_mode == RF_SAMPLE_FIRST_FRAME) a.pass[0] = ArmPass{tb->local_pos, g.HW, 1, {0}};
-    else a.pass[0] = ArmPass{tb->global_pos, tb->nG, g.omega, {0}};
-    a.pass[1] = ArmPass{tb->global_frame, tb->nG, g.omega, {0}};
+    if (sample_mode == RF_SAMPLE_FIRST_FRAME) a.pass[0] = ArmPass{tb->local_pos, tb->local_pos_range, g.HW, 1, {0}};
+    else a.pass[0] = ArmPass{tb->global_pos, tb->global_pos_range, tb->nG, g.omega, {0}};
+    a.pass[1] = ArmPass{tb->global_frame, tb->global_frame_range, tb->nG, g.omega, {0}};
     for (int k = 0; k < n_bw; ++k) {
         a.pass[0].radius[k] = r_temporal[k];
         a.pass[1].radius[k] = r_spatial[k];

@@ -4,25 +4,42 @@
 // (R-tilde).  A pass is described by its sample (sample a is token a * stride), an integer
 // attribute per sample (in-frame position, resp. frame index) and a radius: the mask keeps
 // |attr[a] - attr[b]| <= radius.  The scores Q'K'^T / sqrt(D) are formed tile by tile with
-// bf16 MFMA and never stored; per sampled query the kernel keeps a running maximum, the
-// softmax denominator over all sampled keys (M_init) and the part of it on kept keys (M').
-// The masks are bands on the attribute, so for most (32 queries, 64 keys) pairs every entry is
-// kept or every entry is dropped; the kernel tells from the attribute ranges of the two sides and
-// applies the mask entry by entry only where the band's edge crosses the pair.
+// bf16 MFMA and never stored; the sampled K' rows go global -> LDS one tile ahead, gathered by
+// index arithmetic (no copy of Q', K' is made).  Per sampled query the kernel keeps a reference for
+// the exponent, the softmax denominator over all sampled keys (M_init) and the part of it on kept
+// keys (M').  The masks are bands on the attribute, so for most (32 queries, 64 keys) pairs every
+// entry is kept or every entry is dropped; the kernel tells from the attribute ranges of the two
+// sides and applies the mask entry by entry only where the band's edge crosses the pair.
 // Per-row recalls go to scratch and are reduced in a fixed order by arm_finish_kernel, which
 // also applies the decision rule.
 #include "rf_device.h"
 
 namespace rf {
 
-constexpr int kArmWaves = 4;  // 128 sampled queries per workgroup
+#ifndef RF_ARM_WAVES
+#define RF_ARM_WAVES 8
+#endif
+constexpr int kArmWaves = RF_ARM_WAVES;  // 32 sampled queries per wavefront
+// as in the attention kernel: the reference in the exponent moves only when a row outgrows it by this
+constexpr float kArmRescaleSlack = 8.f;
+
+template <int D>
+struct ArmSmem {
+    using ST = DirectTile<D, kArmWaves>;
+    static constexpr int K_OFF = 0;                      // two K' tiles
+    static constexpr int ATTR_OFF = 2 * ST::K_BYTES;     // per tile: the 64 samples' attributes, then their minimum and maximum
+    static constexpr int ATTR_SLOT = kTileK + 2;
+    static constexpr int BYTES = ATTR_OFF + 2 * ATTR_SLOT * 4 + 16;
+    static_assert(ST::K_BYTES % 256 == 0, "tile buffers must start at multiples of 256 bytes (see DirectTile::k_address)");
+};
 
 template <int D>
 __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, int nQB) {
-    constexpr int NW = kArmWaves, NT = 64 * NW, BQ = 32 * NW;
-    using KT = KTile<D, NT>;
-    __shared__ __attribute__((aligned(16))) unsigned char kbuf[2 * KT::BYTES];
-    __shared__ int abuf[2 * (kTileK + 2)];  // per buffer: the tile's 64 attributes, then their minimum and maximum
+    constexpr int NW = kArmWaves, BQ = 32 * NW;
+    using SM = ArmSmem<D>;
+    using ST = typename SM::ST;
+    extern __shared__ __attribute__((aligned(256))) unsigned char smem[];  // the kernel's only LDS: starts at address 0
+    int* abuf = reinterpret_cast<int*>(smem + SM::ATTR_OFF);
 
     const int item = xcd_contiguous_item(blockIdx.x, nQB * 2 * a.BH);
     if (item < 0) return;
@@ -35,7 +52,7 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
     // samples are video tokens; first_video_row is where those start in the tensors
     const size_t head_off = (static_cast<size_t>(bh) * a.N + a.first_video_row) * D;
     const uint16_t* Qh = a.Q + head_off;
-    const uint16_t* Kh = a.K + head_off;
+    const unsigned char* Kh = reinterpret_cast<const unsigned char*>(a.K + head_off);
 
     const int qs = qb * BQ + wave * 32 + m;  // this lane's sampled query
     const int qsc = min(qs, n - 1);
@@ -52,49 +69,48 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
     q_min = __builtin_amdgcn_readfirstlane(q_min);
     q_max = __builtin_amdgcn_readfirstlane(q_max);
 
-    float m_run = -INFINITY, l_all = 0.f, l_kept[kMaxBw];
+    // m_ref: reference subtracted inside exp2 (raw score units); l_all / l_kept: this lane's share of
+    // the denominator over all sampled keys and over the kept ones, both relative to m_ref
+    float m_ref = 0.f, l_all = 0.f, l_kept[kMaxBw];
+    bool has_ref = false;
 #pragma unroll
     for (int b = 0; b < kMaxBw; ++b) l_kept[b] = 0.f;
     const int n_bw = a.n_bw;
     const float c = a.scale_log2;
     const int ntiles = (n + kTileK - 1) / kTileK;
 
-    KT kt;
+    ST st;
+    st.init(tid);
+    auto k_lds = [&](int t) { return smem + SM::K_OFF + (t & 1) * ST::K_BYTES; };
     int attr_reg = 0;
     auto fetch_tile = [&](int t) {
         const int k0 = t * kTileK;
-        kt.fetch(Kh, tid, [&](int r) { return min(k0 + r, n - 1) * ps.stride; });
+        if (ps.stride == 1 && k0 + kTileK <= n)
+            st.template issue_consecutive<false>(Kh + static_cast<size_t>(k0) * (2 * D), nullptr, k_lds(t), nullptr);
+        else
+            st.template issue<false>(Kh, nullptr, k_lds(t), nullptr, [&](int r) { return min(k0 + r, n - 1) * ps.stride; });
+        // the tile's attributes, and (two more threads) their range from the host-built table
         if (tid < kTileK) attr_reg = ps.attr[min(k0 + tid, n - 1)];
+        else if (tid < kTileK + 2) attr_reg = ps.tile_range[2 * t + tid - kTileK];
     };
-    auto stash_tile = [&](int t) {
-        kt.stash(kbuf + (t & 1) * KT::BYTES, tid);
-        if (tid < kTileK) {  // the first wavefront: attributes, and their range by a butterfly over its 64 lanes
-            int* ab = abuf + (t & 1) * (kTileK + 2);
-            ab[tid] = attr_reg;
-            int lo = attr_reg, hi = attr_reg;
-#pragma unroll
-            for (int w = 1; w < 64; w <<= 1) {
-                lo = min(lo, __shfl_xor(lo, w, 64));
-                hi = max(hi, __shfl_xor(hi, w, 64));
-            }
-            if (tid == 0) {
-                ab[kTileK] = lo;
-                ab[kTileK + 1] = hi;
-            }
-        }
+    auto stash_attr = [&](int t) {
+        if (tid < kTileK + 2) abuf[(t & 1) * SM::ATTR_SLOT + tid] = attr_reg;
     };
     fetch_tile(0);
-    stash_tile(0);
+    stash_attr(0);
+    ST::template wait_landed<0>();
     __syncthreads();
+    // the compiler cannot see the tile loads; make its own wait for the Q loads happen here, not in the loop
+#pragma unroll
+    for (int cc = 0; cc < D / 16; ++cc) asm volatile("" ::"v"(__builtin_bit_cast(u32x4, qf[cc])));
 
     for (int t = 0; t < ntiles; ++t) {
         if (t + 1 < ntiles) fetch_tile(t + 1);
-        const unsigned char* kl = kbuf + (t & 1) * KT::BYTES;
-        const int* al = abuf + (t & 1) * (kTileK + 2);
+        const int* al = abuf + (t & 1) * SM::ATTR_SLOT;
         const int k0 = t * kTileK;
 
         f32x16 s[2];
-        score_tile<D, NT>(kl, qf, m, hf, s);
+        st.template scores<kAheadK>(st.k_address(k_lds(t)), qf, s);
         if (k0 + kTileK > n) {  // ragged last tile: samples past the end do not exist
 #pragma unroll
             for (int kb2 = 0; kb2 < 2; ++kb2)
@@ -107,10 +123,22 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
         for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
             for (int r = 0; r < 16; ++r) mt = fmaxf(mt, s[kb2][r]);
-        mt = fmaxf(mt, other_half(mt));
-        const float m_new = fmaxf(m_run, mt);  // finite: every tile holds at least one real sample
-        const float alpha = fast_exp2((m_run - m_new) * c);
-        const float mc = m_new * c;
+        // the two halves of the wavefront hold different keys of the same 32 queries: their maxima are
+        // exchanged, and the sums rescaled, only when some lane asks for the reference to move
+        const bool grow = has_ref ? (mt - m_ref) * c > kArmRescaleSlack : mt > -INFINITY;
+        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+            mt = fmaxf(mt, other_half(mt));
+            if (mt > -INFINITY) {
+                const float m_new = has_ref ? fmaxf(m_ref, mt) : mt;
+                const float alpha = has_ref ? fast_exp2((m_ref - m_new) * c) : 0.f;  // nothing accumulated before
+                l_all *= alpha;
+#pragma unroll
+                for (int b = 0; b < kMaxBw; ++b) l_kept[b] *= alpha;
+                m_ref = m_new;
+                has_ref = true;
+            }
+        }
+        const float mc = m_ref * c;
         float sum_all = 0.f, sum_kept[kMaxBw];
 #pragma unroll
         for (int b = 0; b < kMaxBw; ++b) sum_kept[b] = 0.f;
@@ -149,12 +177,12 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
                     }
                 }
         }
-        l_all = l_all * alpha + sum_all;
+        l_all += sum_all;
 #pragma unroll
-        for (int b = 0; b < kMaxBw; ++b) l_kept[b] = l_kept[b] * alpha + sum_kept[b];
-        m_run = m_new;
+        for (int b = 0; b < kMaxBw; ++b) l_kept[b] += sum_kept[b];
 
-        if (t + 1 < ntiles) stash_tile(t + 1);
+        if (t + 1 < ntiles) stash_attr(t + 1);
+        ST::template wait_landed<0>();
         __syncthreads();
     }
     l_all += other_half(l_all);
@@ -210,7 +238,7 @@ template <int D>
 static int launch_arm_d(const ArmArgs& a, hipStream_t st) {
     const int nQB = (a.max_n + 32 * kArmWaves - 1) / (32 * kArmWaves);
     const int total = nQB * 2 * a.BH;
-    hipLaunchKernelGGL((arm_recall_kernel<D>), dim3(8 * ((total + 7) / 8)), dim3(64 * kArmWaves), 0, st, a, nQB);
+    hipLaunchKernelGGL((arm_recall_kernel<D>), dim3(8 * ((total + 7) / 8)), dim3(64 * kArmWaves), ArmSmem<D>::BYTES, st, a, nQB);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return static_cast<int>(e);
     hipLaunchKernelGGL(arm_finish_kernel, dim3(a.BH), dim3(256), 0, st, a);

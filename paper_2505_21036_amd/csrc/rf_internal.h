@@ -109,6 +109,7 @@ struct AttnArgs {
 // |attr[a] - attr[b]| <= radius.
 struct ArmPass {
     const int32_t* attr;  // device [n]
+    const int32_t* tile_range;  // device [ceil(n / kTileK)][2]: minimum and maximum attribute of each 64-sample tile
     int n;                // number of samples
     int stride;           // token stride between samples
     int radius[kMaxBw];   // one band half-width per candidate bandwidth
