@@ -284,3 +284,21 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     assert lib.rf_plan_host(C.byref(L), None, 48, 0, None, None, 0, C.byref(needed)) == -5
     small = (C.c_int32 * 2)()
     assert lib.rf_plan_host(C.byref(L), None, 64, 0, None, small, 2, C.byref(needed)) == -6 and needed.value == 10
+
+
+def test_bench_refuses_more_than_one_gpu_and_counts_kept_pairs():
+    """bench.py --gpus N with N > 1 exits with a message (this build is one GPU); its FLOP bookkeeping
+    (kept token pairs per pattern) matches a count over the oracle's mask on a small layout."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in (r.stderr + r.stdout)
+    sys.path.insert(0, ROOT)
+    import bench
+    import rf_inputs as inp
+    w = inp.Workload("count", 1, 1, 64, 5, 6, 11, 19, 64, 1)
+    L = orc.Layout(w.T, w.H, w.W, w.text_len)
+    for cls in (orc.SPATIAL, orc.TEMPORAL, orc.TEXTURAL, orc.DENSE):
+        for bw, tau in ((0.25, 2), (0.13, 3)):
+            want = int(orc.keep_matrix(cls, L, orc.Params(bw, bw, tau)).sum())
+            assert bench.kept_pairs(cls, w, bw, bw, tau) == want, (cls, bw, tau)
