@@ -25,7 +25,7 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 # --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/attn_kernel_hunyuan720p.md: counter
 # values in KiB, FETCH_SIZE scaled x2.0 and WRITE_SIZE x1.0 (what the same counters read for a
 # 1 GiB device copy).  Only known for the workload / block it was profiled on.
-MEASURED_TRAFFIC_BYTES = {("hunyuan720p", 256): (2.0 * 1.8796e7 + 1.0 * 7.147e5) * 1024}
+MEASURED_TRAFFIC_BYTES = {("hunyuan720p", 256): (2.0 * 1.8893e7 + 1.0 * 7.147e5) * 1024}
 
 
 def kept_pairs(cls, w, bw_s=0.25, bw_t=0.25, tau=2):
