@@ -133,10 +133,15 @@ def item_trace(torch, rf, launch, w, block, what):
     trace = torch.zeros(items * 4, dtype=torch.int64, device="cuda:0")
     launch()
     torch.cuda.synchronize()
-    assert rf.load_library().rf_debug_set_trace(C.c_void_p(trace.data_ptr())) == 0
+    lib = rf.load_library()
+    stalls = (C.c_ulonglong * 5)()
+    assert lib.rf_debug_read_stalls(stalls) == 0  # zeroes the sums of the warm-up launch
+    assert lib.rf_debug_set_trace(C.c_void_p(trace.data_ptr())) == 0
     launch()
     torch.cuda.synchronize()
-    assert rf.load_library().rf_debug_set_trace(None) == 0
+    assert lib.rf_debug_set_trace(None) == 0
+    assert lib.rf_debug_read_stalls(stalls) == 0
+    loop_cycles, wait_load, wait_barrier, tiles_walked, issue = (int(v) for v in stalls)
     t = trace.cpu().numpy().reshape(items, 4)
     assert (t[:, 1] > 0).all(), "some item was not processed"
     t0 = t[:, 0].min()
@@ -158,6 +163,10 @@ def item_trace(torch, rf, launch, w, block, what):
             gaps.append(float((s_[1:] - e_[:-1]).mean()))
     return {"workload": w.name, "classes": what, "block": block, "items": items, "workgroups": int(len(np.unique(wg))),
             "span_us": round(float(end.max()), 1), "mean_gap_between_items_us": round(float(np.mean(gaps)), 2) if gaps else None,
+            "first_wavefront_cycles_per_tile": {"in_tile_loop": round(loop_cycles / max(tiles_walked, 1), 1),
+                                                "issuing_tile_loads": round(issue / max(tiles_walked, 1), 1),
+                                                "waiting_for_tile_loads": round(wait_load / max(tiles_walked, 1), 1),
+                                                "at_tile_barrier": round(wait_barrier / max(tiles_walked, 1), 1)},
             "per_xcd": rows}
 
 
@@ -178,9 +187,10 @@ def main():
     ap.add_argument("--probe", action="store_true",
                     help="instead of the step: what the box sustains on MFMA alone (a short and a long burst) and on "
                          "the attention kernel's instruction mix without memory traffic; prints one JSON line")
-    ap.add_argument("--clocks", action="store_true",
-                    help="instead of the step: loop the dense attention launch for a few seconds and sample "
-                         "rocm-smi's shader clock meanwhile; prints one JSON line")
+    ap.add_argument("--clocks", nargs="?", const="dense", default="",
+                    help="instead of the step: loop one attention launch ('dense' if not named; 'spatial', 'temporal', "
+                         "'textural', 'thirds') for a few seconds and sample rocm-smi's shader clock meanwhile; "
+                         "prints one JSON line")
     ap.add_argument("--item-trace", default="",
                     help="instead of the step: one attention launch ('dense', 'spatial', 'temporal', 'textural' or "
                          "'thirds') with the diagnostic library (python -m paper_2505_21036_amd.build --trace), which "
@@ -240,13 +250,14 @@ def main():
         torch.cuda.synchronize()
         return sum(a.elapsed_time(b) for a, b in pairs) / reps
 
+    if args.clocks or args.item_trace:
+        one = {"dense": dense, "thirds": thirds, "spatial": torch.zeros_like(dense), "temporal": torch.ones_like(dense),
+               "textural": torch.full_like(dense, 2)}[args.clocks or args.item_trace]
     if args.clocks:
-        print(json.dumps({"clocks": sample_clocks(torch, lambda: attn(dense))}))
+        print(json.dumps({"clocks": dict(classes=args.clocks, **sample_clocks(torch, lambda: attn(one)))}))
         return
 
     if args.item_trace:
-        one = {"dense": dense, "thirds": thirds, "spatial": torch.zeros_like(dense), "temporal": torch.ones_like(dense),
-               "textural": torch.full_like(dense, 2)}[args.item_trace]
         print(json.dumps({"item_trace": item_trace(torch, rf, lambda: attn(one), w, block, args.item_trace)}))
         return
 
