@@ -283,6 +283,12 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
         // than 2^kRescaleSlack (or has none yet): the softmax does not depend on the reference.
         f32x16 s[2];
         scores(t, e_cur, s);
+        // With eight wavefronts at head_dim 128 the softmax section (VALU only) runs at raised
+        // priority and the two MFMA sections at the default: the wavefront that shares the SIMD is
+        // then served in the gaps of this one's VALU work rather than the other way round (measured
+        // +1 % there; neutral at head_dim 96 and 1-4 % slower with four wavefronts, so not there).
+        constexpr bool kSoftmaxPriority = D == 128 && NW == 8;
+        if (kSoftmaxPriority) __builtin_amdgcn_s_setprio(1);
         float mt = s[0][0];
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2)
@@ -320,6 +326,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
                 l_run = add_bf16_pair(add_bf16_pair(add_bf16_pair(add_bf16_pair(l_run, w.x), w.y), w.z), w.w);
                 pf[2 * kb2 + u2] = as_bf16x8(w);
             }
+        if (kSoftmaxPriority) __builtin_amdgcn_s_setprio(0);
         accumulate(t);
 
         // tile t+1 must be in LDS at the barrier; the loads of the tiles after it may stay in flight
