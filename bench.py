@@ -48,128 +48,6 @@ def kept_pairs(cls, w, bw_s=0.25, bw_t=0.25, tau=2):
     return vv + tl * N + Nv * tl  # text rows see everything, video rows see every text key
 
 
-def mfma_probe(torch, dev):
-    """TFLOP/s of v_mfma_f32_32x32x16_bf16 alone (a burst of ~15 ms, then ~2 s of back-to-back launches, where
-    the clock has settled) and of the attention kernel's per-MFMA instruction mix, from librf_probe.so."""
-    import ctypes as C
-
-    from paper_2505_21036_amd.build import PROBE_LIB
-    if not os.path.exists(PROBE_LIB):
-        sys.exit("bench.py --probe: librf_probe.so is not built (python -m paper_2505_21036_amd.build)")
-    lib = C.CDLL(PROBE_LIB)
-    lib.rf_probe_launch.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
-    lib.rf_probe_flops.restype = C.c_double
-    lib.rf_probe_flops.argtypes = [C.c_int, C.c_int]
-    cus = torch.cuda.get_device_properties(dev).multi_processor_count
-    out = torch.empty(cus * 512, dtype=torch.float32, device=dev)
-    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
-
-    def rate(mix, iters, launches):
-        assert lib.rf_probe_launch(mix, cus, 100, out.data_ptr(), stream) == 0
-        torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(launches):
-            assert lib.rf_probe_launch(mix, cus, iters, out.data_ptr(), stream) == 0
-        b.record()
-        torch.cuda.synchronize()
-        return lib.rf_probe_flops(cus, iters) * launches / (a.elapsed_time(b) * 1e-3) / 1e12
-
-    res = {"cus": cus, "mfma_burst_tflops": round(rate(0, 20000, 1), 1)}
-    time.sleep(1.0)
-    res["mfma_sustained_tflops"] = round(rate(0, 20000, 120), 1)
-    time.sleep(1.0)
-    res["attention_mix_burst_tflops"] = round(rate(1, 20000, 1), 1)
-    res["attention_mix_sustained_tflops"] = round(rate(1, 20000, 60), 1)
-    res["note"] = "mix = per MFMA one exp2 and four other fp32 VALU instructions, no memory traffic, no dependence on the MFMAs"
-    return res
-
-
-def sample_clocks(torch, launch, seconds=4.0):
-    """Shader clock as rocm-smi reports it, sampled every 0.5 s while `launch` is repeated."""
-    import re
-    import subprocess
-    import threading
-
-    def sclk():
-        try:
-            txt = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=10).stdout
-        except Exception as e:  # rocm-smi missing or not permitted: report it, do not fail the run
-            return "rocm-smi: %s" % e
-        m = re.search(r"sclk clock level:[^(]*\((\d+)Mhz\)", txt)
-        return int(m.group(1)) if m else None
-
-    idle = sclk()
-    launch()
-    torch.cuda.synchronize()
-    samples, stop = [], threading.Event()
-
-    def sampler():
-        while not stop.is_set():
-            samples.append(sclk())
-            stop.wait(0.5)
-
-    th = threading.Thread(target=sampler)
-    t0 = time.perf_counter()
-    th.start()
-    n = 0
-    while time.perf_counter() - t0 < seconds:
-        launch()
-        torch.cuda.synchronize()
-        n += 1
-    stop.set()
-    th.join()
-    return {"idle_mhz": idle, "under_load_mhz": samples, "launches": n, "ms_per_launch": round((time.perf_counter() - t0) * 1e3 / n, 3)}
-
-
-def item_trace(torch, rf, launch, w, block, what):
-    """Per-XCD statistics of one attention launch of the diagnostic library: which XCD processed how many
-    items (and how many of them came from another XCD's queue), when it finished, its time per key tile."""
-    import ctypes as C
-
-    import numpy as np
-    nqb = -(-w.N // block)
-    items = nqb * w.B * w.nH
-    trace = torch.zeros(items * 4, dtype=torch.int64, device="cuda:0")
-    launch()
-    torch.cuda.synchronize()
-    lib = rf.load_library()
-    stalls = (C.c_ulonglong * 5)()
-    assert lib.rf_debug_read_stalls(stalls) == 0  # zeroes the sums of the warm-up launch
-    assert lib.rf_debug_set_trace(C.c_void_p(trace.data_ptr())) == 0
-    launch()
-    torch.cuda.synchronize()
-    assert lib.rf_debug_set_trace(None) == 0
-    assert lib.rf_debug_read_stalls(stalls) == 0
-    loop_cycles, wait_load, wait_barrier, tiles_walked, issue = (int(v) for v in stalls)
-    t = trace.cpu().numpy().reshape(items, 4)
-    assert (t[:, 1] > 0).all(), "some item was not processed"
-    t0 = t[:, 0].min()
-    start, end = (t[:, 0] - t0) / 100.0, (t[:, 1] - t0) / 100.0  # 100 MHz ticks -> us
-    ntiles, wg, queue = t[:, 2] & 0xffffffff, t[:, 2] >> 32, t[:, 3] >> 32
-    xcd = wg & 7
-    rows = []
-    for x in range(8):
-        m = xcd == x
-        rows.append({"xcd": x, "items": int(m.sum()), "from_other_queues": int((m & (queue != x)).sum()),
-                     "last_end_us": round(float(end[m].max()), 1),
-                     "us_per_tile": round(float((end[m] - start[m]).sum() / max(int(ntiles[m].sum()), 1)), 3)})
-    gaps = []
-    for g in np.unique(wg):
-        m = wg == g
-        o = np.argsort(start[m])
-        s_, e_ = start[m][o], end[m][o]
-        if len(s_) > 1:
-            gaps.append(float((s_[1:] - e_[:-1]).mean()))
-    return {"workload": w.name, "classes": what, "block": block, "items": items, "workgroups": int(len(np.unique(wg))),
-            "span_us": round(float(end.max()), 1), "mean_gap_between_items_us": round(float(np.mean(gaps)), 2) if gaps else None,
-            "first_wavefront_cycles_per_tile": {"in_tile_loop": round(loop_cycles / max(tiles_walked, 1), 1),
-                                                "issuing_tile_loads": round(issue / max(tiles_walked, 1), 1),
-                                                "waiting_for_tile_loads": round(wait_load / max(tiles_walked, 1), 1),
-                                                "at_tile_barrier": round(wait_barrier / max(tiles_walked, 1), 1)},
-            "per_xcd": rows}
-
-
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -184,27 +62,10 @@ def main():
     ap.add_argument("--plus", action="store_true",
                     help="instead of the step: time RainFusion+ (per-head bandwidth from 0.5/0.25/0.125) on the "
                          "planted workload, whose heads the ARM can tell apart; prints one JSON line")
-    ap.add_argument("--probe", action="store_true",
-                    help="instead of the step: what the box sustains on MFMA alone (a short and a long burst) and on "
-                         "the attention kernel's instruction mix without memory traffic; prints one JSON line")
-    ap.add_argument("--clocks", nargs="?", const="dense", default="",
-                    help="instead of the step: loop one attention launch ('dense' if not named; 'spatial', 'temporal', "
-                         "'textural', 'thirds') for a few seconds and sample rocm-smi's shader clock meanwhile; "
-                         "prints one JSON line")
-    ap.add_argument("--item-trace", default="",
-                    help="instead of the step: one attention launch ('dense', 'spatial', 'temporal', 'textural' or "
-                         "'thirds') with the diagnostic library (python -m paper_2505_21036_amd.build --trace), which "
-                         "timestamps every (head, query block) item; prints per-XCD statistics as one JSON line")
     ap.add_argument("--only", default="", help="profiling aid: run just 'step', 'arm', 'thirds', 'dense', every head 'spatial' / 'temporal' / 'textural', or 'copy' (a 1 GiB device copy)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
-
-    if args.item_trace:  # must be chosen before the binding loads a library
-        TRACE_LIB = os.path.join(ROOT, "paper_2505_21036_amd", "librainfusion_trace.so")
-        if not os.path.exists(TRACE_LIB):
-            sys.exit("bench.py --item-trace: build the diagnostic library first (python -m paper_2505_21036_amd.build --trace)")
-        os.environ["RF_LIBRARY"] = TRACE_LIB
 
     import torch
 
@@ -213,9 +74,6 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
-    if args.probe:
-        print(json.dumps({"probe": mfma_probe(torch, dev)}))
-        return
     w = inp.WORKLOADS[args.workload]
     block = args.block or w.block
     rl = rf.rf_layout(w.T, w.H, w.W, w.text_len)
@@ -249,17 +107,6 @@ def main():
             pairs.append((a, b))
         torch.cuda.synchronize()
         return sum(a.elapsed_time(b) for a, b in pairs) / reps
-
-    if args.clocks or args.item_trace:
-        one = {"dense": dense, "thirds": thirds, "spatial": torch.zeros_like(dense), "temporal": torch.ones_like(dense),
-               "textural": torch.full_like(dense, 2)}[args.clocks or args.item_trace]
-    if args.clocks:
-        print(json.dumps({"clocks": dict(classes=args.clocks, **sample_clocks(torch, lambda: attn(one)))}))
-        return
-
-    if args.item_trace:
-        print(json.dumps({"item_trace": item_trace(torch, rf, lambda: attn(one), w, block, args.item_trace)}))
-        return
 
     if args.sweep:
         attn(dense)

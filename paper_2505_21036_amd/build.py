@@ -7,8 +7,6 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librainfusion.so")
-TRACE_LIB = os.path.join(HERE, "librainfusion_trace.so")  # diagnostic build: per-item timestamps (-DRF_TRACE)
-PROBE_LIB = os.path.join(HERE, "librf_probe.so")          # benchmark yardsticks (MFMA-only loops), not the product
 SOURCES = ["rf_api.cpp", "rf_plan.cpp", "rf_attn.hip", "rf_arm.hip"]
 HEADERS = ["rf_internal.h", "rf_device.h"]
 
@@ -58,18 +56,5 @@ def build_library(verbose=False, extra_flags=(), out=LIB):
     return out
 
 
-def build_probe(out=PROBE_LIB):
-    """The benchmark's MFMA yardstick kernels, a library of their own."""
-    tmp = out + ".tmp%d" % os.getpid()
-    subprocess.check_call([hipcc()] + compile_flags() + ["-shared", os.path.join(CSRC, "rf_probe.hip"), "-o", tmp],
-                          stderr=subprocess.DEVNULL)
-    os.replace(tmp, out)
-    return out
-
-
 if __name__ == "__main__":
-    if "--trace" in sys.argv:
-        print(build_library(verbose=True, extra_flags=["-DRF_TRACE"], out=TRACE_LIB))
-    else:
-        print(build_library(verbose=True))
-        print(build_probe())
+    print(build_library(verbose=True))

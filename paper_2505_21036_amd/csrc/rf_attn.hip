@@ -61,24 +61,6 @@ struct QueryBlock {
 // softmax is invariant to the reference, so a stale one only costs range, which fp32/bf16 have.
 constexpr float kRescaleSlack = 8.f;
 
-#ifdef RF_TRACE
-// Diagnostic build only: per workgroup, wall-clock ticks (100 MHz) at entry and exit and the
-// number of tiles walked, into a buffer set with rf_debug_set_trace(); and, summed over the first
-// wavefront of every workgroup, shader-clock cycles spent in the tile loop, of them waiting for the
-// next tile's loads to land, of them at the per-tile barrier, the tiles walked, and the cycles spent
-// issuing the tile loads (g_stall[0..4]).
-__device__ unsigned long long* g_trace = nullptr;
-__device__ unsigned long long g_stall[5] = {0, 0, 0, 0, 0};
-extern "C" int rf_debug_set_trace(void* p) { return static_cast<int>(hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &p, sizeof(p))); }
-// Copies the five sums to out (host memory) after the device has drained, then zeroes them.
-extern "C" int rf_debug_read_stalls(unsigned long long* out) {
-    hipError_t e = hipDeviceSynchronize();
-    if (e == hipSuccess) e = hipMemcpyFromSymbol(out, HIP_SYMBOL(g_stall), 5 * sizeof(unsigned long long));
-    const unsigned long long zero[5] = {0, 0, 0, 0, 0};
-    if (e == hipSuccess) e = hipMemcpyToSymbol(HIP_SYMBOL(g_stall), zero, sizeof(zero));
-    return static_cast<int>(e);
-}
-#endif
 
 template <int D, int NW, int MODE>
 __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, const QueryBlock& qk, unsigned char* smem) {
@@ -261,20 +243,10 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
 #pragma unroll
     for (int cc = 0; cc < D / 16; ++cc) asm volatile("" ::"v"(__builtin_bit_cast(u32x4, qf[cc])));
 
-#ifdef RF_TRACE
-    long long stall_load = 0, stall_barrier = 0, issue_cycles = 0;
-    const long long loop_c0 = clock64();
-#endif
     for (int t = 0; t < ntiles; ++t) {
         // the buffer of tile t+AHEAD held tile t+AHEAD-DEPTH, which every wavefront left before the last barrier
         if (t + DEPTH < ntiles) e[DEPTH] = entry_of(t + DEPTH);
-#ifdef RF_TRACE
-        const long long ci = clock64();
-#endif
         if (t + AHEAD < ntiles) fetch_tile(t + AHEAD, e[AHEAD]);
-#ifdef RF_TRACE
-        issue_cycles += clock64() - ci;
-#endif
         if (t + DEPTH < ntiles) load_side(e[DEPTH]);
         const int e_cur = e[0];
 
@@ -330,32 +302,13 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
         accumulate(t);
 
         // tile t+1 must be in LDS at the barrier; the loads of the tiles after it may stay in flight
-#ifdef RF_TRACE
-        const long long c0 = clock64();
-#endif
         if (AHEAD > 1 && t + AHEAD < ntiles) ST::template wait_landed<AHEAD - 1>();
         else ST::template wait_landed<0>();
-#ifdef RF_TRACE
-        const long long c1 = clock64();
-#endif
         if (t + DEPTH < ntiles) stash_side(t + DEPTH, e[DEPTH]);
 #pragma unroll
         for (int i = 0; i < DEPTH; ++i) e[i] = e[i + 1];
         __syncthreads();
-#ifdef RF_TRACE
-        stall_load += c1 - c0;
-        stall_barrier += clock64() - c1;
-#endif
     }
-#ifdef RF_TRACE
-    if (threadIdx.x == 0) {
-        atomicAdd(&g_stall[0], static_cast<unsigned long long>(clock64() - loop_c0));
-        atomicAdd(&g_stall[1], static_cast<unsigned long long>(stall_load));
-        atomicAdd(&g_stall[2], static_cast<unsigned long long>(stall_barrier));
-        atomicAdd(&g_stall[3], static_cast<unsigned long long>(ntiles));
-        atomicAdd(&g_stall[4], static_cast<unsigned long long>(issue_cycles));
-    }
-#endif
     // Eq. 2: divide by the softmax denominator and store.  Lane (hf, m) owns query m and, per
     // 32-channel block, channels 8*(r/4) + 4*hf + r%4.
     const float l_tot = l_run + other_half(l_run);
@@ -470,9 +423,6 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xc
         bh = j / share;
         ordinal = qs.nTB + xcd * qs.per_xcd + j % share;
     }
-#ifdef RF_TRACE
-    const unsigned long long trace_t0 = wall_clock64();
-#endif
     QueryBlock qk;
     qk.bh = bh;
     // per-head bandwidth: the plans differ only in the Spatial / Temporal lists, radii and block order
@@ -533,15 +483,6 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xc
         qk.keyN = pl.N;
         attend<D, NW, MODE_LISTED>(a, pl, qk, smem);
     }
-#ifdef RF_TRACE
-    if (g_trace && threadIdx.x == 0) {
-        unsigned long long* rec = g_trace + 4 * (static_cast<size_t>(qk.bh) * (qs.nVB + qs.nTB) + ordinal);
-        rec[0] = trace_t0;
-        rec[1] = wall_clock64();
-        rec[2] = (static_cast<unsigned long long>(blockIdx.x) << 32) | static_cast<unsigned>(qk.ntiles);
-        rec[3] = (static_cast<unsigned long long>(xcd) << 32) | static_cast<unsigned>(qk.qb);
-    }
-#endif
 }
 
 // Copies of K and V in the order their head walks them, into the caller's workspace: for a
