@@ -6,8 +6,9 @@
  *
  * Conventions for every entry point
  *   - Tensors are DEVICE pointers owned by the caller: bf16, contiguous
- *     [B, nH, N, D] (batch, head, token, channel).  The library neither frees nor
- *     keeps them.  D is 64, 96 or 128.
+ *     [B, nH, N, D] (batch, head, token, channel), 16-byte aligned (the kernels move 16
+ *     bytes at a time; RF_ERR_ALIGN otherwise).  The library neither frees nor keeps
+ *     them.  D is 64, 96 or 128.
  *   - Token order (Sec. 3.1): T frames of H*W tokens each, frame-major, row-major
  *     inside a frame; text_len text tokens follow the video tokens, or precede
  *     them under RF_FLAG_TEXT_FIRST.  N = T*H*W + text_len.
@@ -16,9 +17,10 @@
  *     (layout, params, block) builds and uploads its block lists synchronously.  After
  *     such a warm-up call a sequence of calls only launches kernels (no memsets, no
  *     allocations) and can be captured into a HIP graph; results are bitwise the same
- *     from call to call.  Each rf_sparse_attention call takes the next of 64 small
- *     library-owned counter sets per device (its work queues), so at most 64 attention
- *     calls, or replays of captured ones, may be in flight on a device at a time.
+ *     from call to call.  All per-call device state lives in the caller's workspaces, so
+ *     any number of calls may be in flight as long as each has its own workspace.  The
+ *     library keeps at most 16 block lists per process (least recently used first out;
+ *     making room synchronises the device).
  *   - Return value: RF_OK or a negative rf_status.  Arguments are validated before
  *     any GPU work, so a bad argument never launches a kernel.
  *   - `params == NULL` selects the paper's defaults (Sec. 4.1: both bandwidths 1/4,
@@ -79,7 +81,8 @@ enum rf_status {
                               threshold not in [0, 1] or NaN */
     RF_ERR_BLOCK = -5,     /* block not 64, 128 or 256 */
     RF_ERR_WORKSPACE = -6, /* a required workspace is NULL, or a workspace is too small or misaligned */
-    RF_ERR_HIP = -7        /* a HIP runtime call failed (allocation, copy or launch) */
+    RF_ERR_HIP = -7,       /* a HIP runtime call failed (allocation, copy or launch) */
+    RF_ERR_ALIGN = -8      /* a tensor is not 16-byte aligned, or the attention workspace not 256-byte aligned */
 };
 
 /*
@@ -135,14 +138,16 @@ int rf_arm_classify_plus(const void *Q, const void *K, int B, int nH, int D, con
  *               output of rf_arm_classify can be passed on without a host round trip.
  *               Values outside 0..3 are treated as RF_DENSE.  May be NULL under RF_FLAG_FORCE_DENSE.
  * O           : device, bf16 [B, nH, N, D], written.
- * workspace   : optional device scratch of at least rf_attention_workspace_bytes() bytes, 16-byte
- *               aligned.  If given, K and V of the heads that profit are first copied into it in a
- *               friendlier order: the kept keys of Textural heads made contiguous (K_C, V_C of Eq. 5),
- *               the tokens of Temporal heads in position-major order (same in-frame position of all
- *               frames adjacent), where the Temporal band is one contiguous run of keys per query
- *               block.  The result is the same as without it.  NULL: no copies.  Contents undefined
- *               afterwards; overlapping calls need separate workspaces.
+ * workspace   : device scratch, 256-byte aligned, REQUIRED: at least RF_ATTENTION_MIN_WORKSPACE bytes
+ *               (the kernel's work-queue counters, zeroed by the call itself).  If it has
+ *               rf_attention_workspace_bytes() bytes or more, K and V of the heads that profit are
+ *               first copied into the rest of it in a friendlier order: the kept keys of Textural heads
+ *               made contiguous (K_C, V_C of Eq. 5), the tokens of Temporal heads in position-major order
+ *               (same in-frame position of all frames adjacent), where the Temporal band is one
+ *               contiguous run of keys per query block.  The result is the same either way.  Contents
+ *               undefined afterwards; calls that overlap in time need separate workspaces.
  */
+#define RF_ATTENTION_MIN_WORKSPACE 256
 int rf_sparse_attention(const void *Q, const void *K, const void *V, const int32_t *head_class, int B,
                         int nH, int D, const rf_layout *layout, const rf_params *params, int block,
                         void *O, void *workspace, size_t workspace_bytes, void *stream);
@@ -159,7 +164,7 @@ int rf_sparse_attention_plus(const void *Q, const void *K, const void *V, const 
                              const rf_layout *layout, const rf_params *params, int block, void *O,
                              void *workspace, size_t workspace_bytes, void *stream);
 
-/* Bytes of the optional workspace of rf_sparse_attention (room for a copy of K and V);
+/* Bytes of the full workspace of rf_sparse_attention (the counters plus room for a copy of K and V);
  * 0 if the arguments are invalid. */
 size_t rf_attention_workspace_bytes(int B, int nH, int D, const rf_layout *layout, const rf_params *params);
 

@@ -18,6 +18,7 @@ RF_FLAG_FORCE_DENSE = 4
 RF_PLAN_PARTIAL = 0x40000000
 RF_KEY_TILE = 64
 RF_LIST_TEMPORAL_POSITION_MAJOR = 4
+RF_ATTENTION_MIN_WORKSPACE = 256
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("RF_LIBRARY") or os.path.join(_HERE, "librainfusion.so")
@@ -185,8 +186,9 @@ def rf_sparse_attention_plus(Q, K, V, head_class, head_bw, bandwidths, layout, p
         out = torch.empty_like(Q)
     n_bw = len(bandwidths)
     bws = (C.c_float * n_bw)(*bandwidths)
-    ws_ptr, ws_bytes = (None, 0) if workspace is None else (workspace.data_ptr(),
-                                                           workspace.numel() * workspace.element_size())
+    if workspace is None:  # the work-queue counters only: no packed copies
+        workspace = torch.empty(RF_ATTENTION_MIN_WORKSPACE, dtype=torch.uint8, device=Q.device)
+    ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     st = load_library().rf_sparse_attention_plus(Q.data_ptr(), K.data_ptr(), V.data_ptr(), head_class.data_ptr(),
                                                  head_bw.data_ptr(), bws, n_bw, B, nH, D, C.byref(layout), _pp(params),
                                                  block, out.data_ptr(), ws_ptr, ws_bytes, _stream())
@@ -202,7 +204,8 @@ def rf_attention_workspace_bytes(B, nH, D, layout, params=None):
 def rf_sparse_attention(Q, K, V, head_class, layout, params=None, block=128, out=None, workspace=None):
     """Sparse attention forward (Eq. 1-5). head_class: int32 device tensor [B, nH] (may be None under
     RF_FLAG_FORCE_DENSE). Returns O.
-    workspace: optional uint8 device tensor of rf_attention_workspace_bytes() bytes (packs K_C, V_C)."""
+    workspace: uint8 device tensor; with rf_attention_workspace_bytes() bytes the call packs K_C, V_C and
+    position-major copies into it; None allocates the RF_ATTENTION_MIN_WORKSPACE bytes every call needs."""
     import torch
     _check_bf16(Q, "Q")
     _check_bf16(K, "K", Q.shape)
@@ -217,8 +220,9 @@ def rf_sparse_attention(Q, K, V, head_class, layout, params=None, block=128, out
         out = torch.empty_like(Q)
     else:
         _check_bf16(out, "out", Q.shape)
-    ws_ptr, ws_bytes = (None, 0) if workspace is None else (workspace.data_ptr(),
-                                                           workspace.numel() * workspace.element_size())
+    if workspace is None:  # the work-queue counters only: no packed copies
+        workspace = torch.empty(RF_ATTENTION_MIN_WORKSPACE, dtype=torch.uint8, device=Q.device)
+    ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     hc_ptr = None if head_class is None else head_class.data_ptr()
     st = load_library().rf_sparse_attention(Q.data_ptr(), K.data_ptr(), V.data_ptr(), hc_ptr, B, nH,
                                             D, C.byref(layout), _pp(params), block, out.data_ptr(), ws_ptr, ws_bytes,

@@ -16,23 +16,26 @@ namespace rf {
 namespace {
 
 struct CachedPlan {
-    Geometry g;
-    int block;  // 0 for the ARM sample tables
+    Geometry g;  // with the fields the lists do not depend on zeroed (see list_key)
+    int block;
     int device;
+    unsigned long long last_use = 0;
     void* blob = nullptr;
     DevicePlan dev{};
-    // ARM tables (block == 0)
-    const int32_t* local_pos = nullptr;   // [HW]   in-frame position of first-frame sample a
-    const int32_t* global_pos = nullptr;  // [nG]   in-frame position of equal-interval sample a
-    const int32_t* global_frame = nullptr;  // [nG] frame of equal-interval sample a
-    const int32_t* local_pos_range = nullptr;  // per 64-sample tile of each table: {min, max}
-    const int32_t* global_pos_range = nullptr;
-    const int32_t* global_frame_range = nullptr;
-    int nG = 0;
 };
 
 std::mutex g_mu;
 std::vector<std::unique_ptr<CachedPlan>> g_plans;
+unsigned long long g_use_counter = 0;
+constexpr size_t kMaxCachedPlans = 16;  // per process; the least recently used one makes room
+
+// The block lists depend on the layout, the band widths, the checkerboard stride and the placement
+// of the text tokens, not on the ARM's sampling interval or its fallback class.
+Geometry list_key(Geometry g) {
+    g.omega = 0;
+    g.two_head = 0;
+    return g;
+}
 
 bool same_geometry(const Geometry& a, const Geometry& b) { return std::memcmp(&a, &b, sizeof(Geometry)) == 0; }
 
@@ -63,12 +66,23 @@ struct BlobBuilder {
     }
 };
 
-int get_attention_plan(const Geometry& g, int block, const DevicePlan** out) {
+// out receives a COPY of the plan: the cache entry may be evicted by a later call (its device memory
+// is only freed after the device has drained, so kernels already launched keep reading valid lists).
+int get_attention_plan(const Geometry& geometry, int block, DevicePlan* out) {
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return RF_ERR_HIP;
+    const Geometry g = list_key(geometry);
     std::lock_guard<std::mutex> lock(g_mu);
     CachedPlan* cp = find_plan(g, block, device);
     if (!cp) {
+        if (g_plans.size() >= kMaxCachedPlans) {
+            size_t oldest = 0;
+            for (size_t i = 1; i < g_plans.size(); ++i)
+                if (g_plans[i]->last_use < g_plans[oldest]->last_use) oldest = i;
+            if (hipDeviceSynchronize() != hipSuccess) return RF_ERR_HIP;
+            if (g_plans[oldest]->blob && hipFree(g_plans[oldest]->blob) != hipSuccess) return RF_ERR_HIP;
+            g_plans.erase(g_plans.begin() + static_cast<std::ptrdiff_t>(oldest));
+        }
         HostPlan hp;
         build_plan(g, block, &hp);
         BlobBuilder bb;
@@ -110,94 +124,25 @@ int get_attention_plan(const Geometry& g, int block, const DevicePlan** out) {
         cp = p.get();
         g_plans.push_back(std::move(p));
     }
-    *out = &cp->dev;
+    cp->last_use = ++g_use_counter;
+    *out = cp->dev;
     return RF_OK;
 }
 
 int global_sample_count(const Geometry& g) { return (g.Nv + g.omega - 1) / g.omega; }
 
-int get_arm_tables(const Geometry& g, const CachedPlan** out) {
-    int device = 0;
-    if (hipGetDevice(&device) != hipSuccess) return RF_ERR_HIP;
-    std::lock_guard<std::mutex> lock(g_mu);
-    CachedPlan* cp = find_plan(g, 0, device);
-    if (!cp) {
-        const int nG = global_sample_count(g);
-        std::vector<int32_t> lp(g.HW), gp(nG), gf(nG);
-        for (int a = 0; a < g.HW; ++a) lp[a] = a;
-        for (int a = 0; a < nG; ++a) {
-            const int64_t tok = static_cast<int64_t>(a) * g.omega;
-            gp[a] = static_cast<int32_t>(tok % g.HW);
-            gf[a] = static_cast<int32_t>(tok / g.HW);
-        }
-        auto tile_ranges = [](const std::vector<int32_t>& v) {
-            std::vector<int32_t> r;
-            for (size_t t0 = 0; t0 < v.size(); t0 += kTileK) {
-                const size_t t1 = std::min(v.size(), t0 + kTileK);
-                r.push_back(*std::min_element(v.begin() + t0, v.begin() + t1));
-                r.push_back(*std::max_element(v.begin() + t0, v.begin() + t1));
-            }
-            return r;
-        };
-        BlobBuilder bb;
-        const size_t o0 = bb.add(lp), o1 = bb.add(gp), o2 = bb.add(gf);
-        const size_t r0 = bb.add(tile_ranges(lp)), r1 = bb.add(tile_ranges(gp)), r2 = bb.add(tile_ranges(gf));
-        auto p = std::make_unique<CachedPlan>();
-        p->g = g;
-        p->block = 0;
-        p->device = device;
-        const int st = bb.upload(&p->blob);
-        if (st != RF_OK) return st;
-        const int32_t* base = static_cast<const int32_t*>(p->blob);
-        p->local_pos = base + o0;
-        p->global_pos = base + o1;
-        p->global_frame = base + o2;
-        p->local_pos_range = base + r0;
-        p->global_pos_range = base + r1;
-        p->global_frame_range = base + r2;
-        p->nG = nG;
-        cp = p.get();
-        g_plans.push_back(std::move(p));
-    }
-    *out = cp;
-    return RF_OK;
-}
-
-// Work-queue counters of the attention kernel: 8 ints per call, taken round-robin from a small
-// per-device ring so that calls in flight on different streams do not share a set.
-constexpr int kQueueSets = 64, kQueueStride = 64;  // ints; a set per 256 bytes
-struct QueueRing {
-    int device;
-    int* base;
-    unsigned next;
-};
-std::vector<QueueRing> g_queues;
-
-int next_queue(int** out) {
-    int device = 0;
-    if (hipGetDevice(&device) != hipSuccess) return RF_ERR_HIP;
-    std::lock_guard<std::mutex> lock(g_mu);
-    for (auto& r : g_queues)
-        if (r.device == device) {
-            *out = r.base + (r.next++ % kQueueSets) * kQueueStride;
-            return RF_OK;
-        }
-    void* p = nullptr;
-    if (hipMalloc(&p, kQueueSets * kQueueStride * sizeof(int)) != hipSuccess) return RF_ERR_HIP;
-    g_queues.push_back(QueueRing{device, static_cast<int*>(p), 1});
-    *out = static_cast<int*>(p);
-    return RF_OK;
-}
-
 bool valid_block(int block) { return block == 64 || block == 128 || block == 256; }  // query rows per block
 
-int check_shape(int B, int nH, int D, const Geometry& g) {
+// (token counts that overflow int32 indices were already refused by resolve_geometry)
+int check_shape(int B, int nH, int D) {
     if (B < 1 || nH < 1) return RF_ERR_SHAPE;
     if (D != 64 && D != 96 && D != 128) return RF_ERR_SHAPE;
     if (static_cast<int64_t>(B) * nH > (1 << 20)) return RF_ERR_SHAPE;
-    (void)g;
     return RF_OK;
 }
+
+// The kernels read and write the tensors 16 bytes at a time.
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 size_t arm_rows(const Geometry& g) { return static_cast<size_t>(std::max(g.HW, global_sample_count(g))); }
 
@@ -220,6 +165,7 @@ const char* rf_status_string(int status) {
         case RF_ERR_BLOCK: return "block must be 64, 128 or 256";
         case RF_ERR_WORKSPACE: return "workspace missing or too small";
         case RF_ERR_HIP: return "HIP runtime error";
+        case RF_ERR_ALIGN: return "tensor or workspace pointer misaligned";
         default: return "unknown status";
     }
 }
@@ -255,8 +201,9 @@ static int arm_classify_impl(const void* Q, const void* K, int B, int nH, int D,
     Geometry g;
     int st = resolve_geometry(layout, params, &g);
     if (st != RF_OK) return st;
-    st = check_shape(B, nH, D, g);
+    st = check_shape(B, nH, D);
     if (st != RF_OK) return st;
+    if (!aligned16(Q) || !aligned16(K)) return RF_ERR_ALIGN;
     if (sample_mode != RF_SAMPLE_FIRST_FRAME && sample_mode != RF_SAMPLE_EQUAL_INTERVAL) return RF_ERR_PARAM;
     if (!(threshold >= 0.f && threshold <= 1.f)) return RF_ERR_PARAM;
     if (bandwidths) {
@@ -280,19 +227,16 @@ static int arm_classify_impl(const void* Q, const void* K, int B, int nH, int D,
         std::stable_sort(a.by_width, a.by_width + n_bw, [&](int x, int y) { return bandwidths[x] < bandwidths[y]; });
     }
 
-    const CachedPlan* tb = nullptr;
-    st = get_arm_tables(g, &tb);
-    if (st != RF_OK) return st;
-
     a.Q = static_cast<const uint16_t*>(Q);
     a.K = static_cast<const uint16_t*>(K);
     a.BH = B * nH;
     a.N = g.N;
     a.first_video_row = g.video_shift();
     a.scale_log2 = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(D)));
-    if (sample_mode == RF_SAMPLE_FIRST_FRAME) a.pass[0] = ArmPass{tb->local_pos, tb->local_pos_range, g.HW, 1, {0}};
-    else a.pass[0] = ArmPass{tb->global_pos, tb->global_pos_range, tb->nG, g.omega, {0}};
-    a.pass[1] = ArmPass{tb->global_frame, tb->global_frame_range, tb->nG, g.omega, {0}};
+    const int nG = global_sample_count(g);
+    if (sample_mode == RF_SAMPLE_FIRST_FRAME) a.pass[0] = ArmPass{0, g.HW, 1, g.HW, {0}};
+    else a.pass[0] = ArmPass{0, nG, g.omega, g.HW, {0}};
+    a.pass[1] = ArmPass{1, nG, g.omega, g.HW, {0}};
     for (int k = 0; k < n_bw; ++k) {
         a.pass[0].radius[k] = r_temporal[k];
         a.pass[1].radius[k] = r_spatial[k];
@@ -327,8 +271,8 @@ int rf_arm_classify_plus(const void* Q, const void* K, int B, int nH, int D, con
 
 size_t rf_attention_workspace_bytes(int B, int nH, int D, const rf_layout* layout, const rf_params* params) {
     Geometry g;
-    if (resolve_geometry(layout, params, &g) != RF_OK || check_shape(B, nH, D, g) != RF_OK) return 0;
-    return 2 * static_cast<size_t>(B) * nH * g.N * D * sizeof(uint16_t);
+    if (resolve_geometry(layout, params, &g) != RF_OK || check_shape(B, nH, D) != RF_OK) return 0;
+    return RF_ATTENTION_MIN_WORKSPACE + 2 * static_cast<size_t>(B) * nH * g.N * D * sizeof(uint16_t);
 }
 
 static int sparse_attention_impl(const void* Q, const void* K, const void* V, const int32_t* head_class,
@@ -341,11 +285,15 @@ static int sparse_attention_impl(const void* Q, const void* K, const void* V, co
     Geometry g;
     int st = resolve_geometry(layout, params, &g);
     if (st != RF_OK) return st;
-    st = check_shape(B, nH, D, g);
+    st = check_shape(B, nH, D);
     if (st != RF_OK) return st;
     if (!valid_block(block)) return RF_ERR_BLOCK;
-    if (workspace && workspace_bytes < rf_attention_workspace_bytes(B, nH, D, layout, params)) return RF_ERR_WORKSPACE;
-    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 15)) return RF_ERR_WORKSPACE;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return RF_ERR_ALIGN;
+    // the work-queue counters live in the first RF_ATTENTION_MIN_WORKSPACE bytes; a workspace of the
+    // full size also has room for the packed copies of K and V
+    if (!workspace || workspace_bytes < RF_ATTENTION_MIN_WORKSPACE) return RF_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255) return RF_ERR_ALIGN;
+    const bool room_to_pack = workspace_bytes >= rf_attention_workspace_bytes(B, nH, D, layout, params);
 
     AttnArgs a{};
     a.n_plans = bandwidths ? n_bw : 1;
@@ -355,23 +303,20 @@ static int sparse_attention_impl(const void* Q, const void* K, const void* V, co
             st = geometry_with_bandwidth(layout, params, bandwidths[k], &gk);
             if (st != RF_OK) return st;
         }
-        const DevicePlan* dp = nullptr;
-        st = get_attention_plan(gk, block, &dp);
+        st = get_attention_plan(gk, block, &a.plan[k]);
         if (st != RF_OK) return st;
-        a.plan[k] = *dp;
     }
     a.Q = static_cast<const uint16_t*>(Q);
     a.K = static_cast<const uint16_t*>(K);
     a.V = static_cast<const uint16_t*>(V);
     a.O = static_cast<uint16_t*>(O);
-    st = next_queue(&a.queue);
-    if (st != RF_OK) return st;
+    a.queue = static_cast<int*>(workspace);
     a.head_class = force_dense ? nullptr : head_class;
     a.head_bw = bandwidths ? head_bw : nullptr;
     a.BH = B * nH;
     a.scale_log2 = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(D)));
-    if (workspace && !force_dense) {
-        a.packed_k = static_cast<uint16_t*>(workspace);
+    if (room_to_pack && !force_dense) {
+        a.packed_k = reinterpret_cast<uint16_t*>(static_cast<unsigned char*>(workspace) + RF_ATTENTION_MIN_WORKSPACE);
         a.packed_v = a.packed_k + static_cast<size_t>(B) * nH * g.N * D;
         if (launch_pack_textural(a, D, stream) != 0) return RF_ERR_HIP;
     }
@@ -447,15 +392,12 @@ int rf_plan_position_major(const rf_layout* layout, const rf_params* params, int
 
 int rf_plan_clear(void) {
     std::lock_guard<std::mutex> lock(g_mu);
-    if (g_plans.empty() && g_queues.empty()) return RF_OK;
+    if (g_plans.empty()) return RF_OK;
     int st = RF_OK;
     if (hipDeviceSynchronize() != hipSuccess) st = RF_ERR_HIP;
     for (auto& p : g_plans)
         if (p->blob && hipFree(p->blob) != hipSuccess) st = RF_ERR_HIP;
     g_plans.clear();
-    for (auto& r : g_queues)
-        if (hipFree(r.base) != hipSuccess) st = RF_ERR_HIP;
-    g_queues.clear();
     return st;
 }
 

@@ -10,8 +10,9 @@
 // keys (M').  The masks are bands on the attribute, so for most (32 queries, 64 keys) pairs every
 // entry is kept or every entry is dropped; the kernel tells from the attribute ranges of the two
 // sides and applies the mask entry by entry only where the band's edge crosses the pair.
-// Per-row recalls go to scratch and are reduced in a fixed order by arm_finish_kernel, which
-// also applies the decision rule.
+// A sample's attribute (in-frame position or frame) follows from its index by arithmetic; no table of
+// samples exists anywhere.  Per-row recalls go to scratch and are reduced in a fixed order by
+// arm_finish_kernel, which also applies the decision rule.
 #include "rf_device.h"
 
 namespace rf {
@@ -27,7 +28,7 @@ template <int D>
 struct ArmSmem {
     using ST = DirectTile<D, kArmWaves>;
     static constexpr int K_OFF = 0;                      // two K' tiles
-    static constexpr int ATTR_OFF = 2 * ST::K_BYTES;     // per tile: the 64 samples' attributes, then their minimum and maximum
+    static constexpr int ATTR_OFF = 2 * ST::K_BYTES;     // per tile: the 64 samples' attributes, then bounds on them (lowest, highest)
     static constexpr int ATTR_SLOT = kTileK + 2;
     static constexpr int BYTES = ATTR_OFF + 2 * ATTR_SLOT * 4 + 16;
     static_assert(ST::K_BYTES % 256 == 0, "tile buffers must start at multiples of 256 bytes (see DirectTile::k_address)");
@@ -58,7 +59,11 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
     const int qsc = min(qs, n - 1);
     bf16x8 qf[D / 16];
     load_q_frags<D>(Qh, qsc * ps.stride, hf, qf);
-    const int q_attr = ps.attr[qsc];
+    auto attr_of = [&](int sample) {
+        const int token = sample * ps.stride;
+        return ps.by_frame ? token / ps.HW : token % ps.HW;
+    };
+    const int q_attr = attr_of(qsc);
     // attribute range of this wavefront's 32 queries (both halves hold the same queries)
     int q_min = q_attr, q_max = q_attr;
 #pragma unroll
@@ -89,12 +94,26 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
             st.template issue_consecutive<false>(Kh + static_cast<size_t>(k0) * (2 * D), nullptr, k_lds(t), nullptr);
         else
             st.template issue<false>(Kh, nullptr, k_lds(t), nullptr, [&](int r) { return min(k0 + r, n - 1) * ps.stride; });
-        // the tile's attributes, and (two more threads) their range from the host-built table
-        if (tid < kTileK) attr_reg = ps.attr[min(k0 + tid, n - 1)];
-        else if (tid < kTileK + 2) attr_reg = ps.tile_range[2 * t + tid - kTileK];
+        // the tile's attributes (first wavefront, one sample per lane)
+        if (tid < kTileK) attr_reg = attr_of(min(k0 + tid, n - 1));
     };
+    // Also bounds on the tile's attributes: samples are in token order, so frames never decrease, and
+    // positions do not either as long as the tile stays inside one frame; a tile that crosses into
+    // another frame gets the widest bounds (the caller then masks it entry by entry, which is exact).
     auto stash_attr = [&](int t) {
-        if (tid < kTileK + 2) abuf[(t & 1) * SM::ATTR_SLOT + tid] = attr_reg;
+        if (tid >= kTileK) return;
+        int* slot = abuf + (t & 1) * SM::ATTR_SLOT;
+        slot[tid] = attr_reg;
+        const int first = t * kTileK * ps.stride, last = min(t * kTileK + kTileK - 1, n - 1) * ps.stride;
+        int lo = __builtin_amdgcn_readlane(attr_reg, 0), hi = __builtin_amdgcn_readlane(attr_reg, kTileK - 1);
+        if (!ps.by_frame && first / ps.HW != last / ps.HW) {
+            lo = 0;
+            hi = ps.HW - 1;
+        }
+        if (tid == 0) {
+            slot[kTileK] = lo;
+            slot[kTileK + 1] = hi;
+        }
     };
     fetch_tile(0);
     stash_attr(0);

@@ -8,6 +8,7 @@
 // MFMA.  In tiles flagged partial the token-level predicate of the pattern is re-applied to each
 // score.
 #include <algorithm>
+#include <mutex>
 
 #include "rf_device.h"
 
@@ -521,23 +522,34 @@ template <int D, int NW>
 static int launch_one(const AttnArgs& a, hipStream_t st) {
     constexpr int NT = 64 * NW;
     constexpr int smem = AttnSmem<D, NW>::BYTES;
-    static int resident = 0;  // workgroups the chip holds at once; set on first use (also raises the dynamic-LDS limit)
-    if (resident == 0) {
-        const void* fn = reinterpret_cast<const void*>(&attn_kernel<D, NW>);
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return static_cast<int>(e);
-        int dev = 0, cus = 0, per_cu = 0;
-        if ((e = hipGetDevice(&dev)) != hipSuccess) return static_cast<int>(e);
-        if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return static_cast<int>(e);
-        if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_kernel<D, NW>, NT, smem)) != hipSuccess)
-            return static_cast<int>(e);
-        if (cus < 1 || per_cu < 1) return static_cast<int>(hipErrorInvalidValue);
-        resident = cus * per_cu;
+    // workgroups each device holds at once, found on first use there (which also raises the kernel's dynamic-LDS limit)
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static int resident_on[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return static_cast<int>(e);
+    if (dev < 0 || dev >= kMaxDevices) return static_cast<int>(hipErrorInvalidDevice);
+    int resident = 0;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (resident_on[dev] == 0) {
+            const void* fn = reinterpret_cast<const void*>(&attn_kernel<D, NW>);
+            e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            if (e != hipSuccess) return static_cast<int>(e);
+            int cus = 0, per_cu = 0;
+            if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return static_cast<int>(e);
+            if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_kernel<D, NW>, NT, smem)) != hipSuccess)
+                return static_cast<int>(e);
+            if (cus < 1 || per_cu < 1) return static_cast<int>(hipErrorInvalidValue);
+            resident_on[dev] = cus * per_cu;
+        }
+        resident = resident_on[dev];
     }
     const long long items = static_cast<long long>(a.plan[0].nQB) * a.BH;
     const int grid = static_cast<int>(std::min<long long>(resident, items));
     hipLaunchKernelGGL(reset_queue_kernel, dim3(1), dim3(64), 0, st, a.queue);
-    hipError_t e = hipGetLastError();
+    e = hipGetLastError();
     if (e != hipSuccess) return static_cast<int>(e);
     hipLaunchKernelGGL((attn_kernel<D, NW>), dim3(grid), dim3(NT), smem, st, a);
     return static_cast<int>(hipGetLastError());

@@ -100,18 +100,18 @@ struct AttnArgs {
     uint16_t* packed_k;
     uint16_t* packed_v;
     const int32_t* head_bw;  // optional per-head index into plan[]; null or out of range: plan[0]
-    int* queue;              // 8 work-queue counters (one per XCD), library-owned, zeroed by the launcher
+    int* queue;              // 8 work-queue counters (one per XCD) at the start of the caller's workspace, zeroed by the launcher
     int n_plans;
     DevicePlan plan[kMaxBw];
 };
 
-// One ARM pass = one (sampling, mask) pair: sample a -> token a * stride, mask keeps
-// |attr[a] - attr[b]| <= radius.
+// One ARM pass = one (sampling, mask) pair: sample a -> video token a * stride, whose attribute is its
+// in-frame position (token mod HW) or its frame (token div HW); the mask keeps |attr[a] - attr[b]| <= radius.
 struct ArmPass {
-    const int32_t* attr;  // device [n]
-    const int32_t* tile_range;  // device [ceil(n / kTileK)][2]: minimum and maximum attribute of each 64-sample tile
+    int by_frame;         // 0: attribute = in-frame position (Temporal mask), 1: attribute = frame (Spatial mask)
     int n;                // number of samples
     int stride;           // token stride between samples
+    int HW;               // tokens per frame
     int radius[kMaxBw];   // one band half-width per candidate bandwidth
 };
 

@@ -163,11 +163,11 @@ def test_text_first_every_class_every_row(name, block):
     for mode in (rf.RF_SAMPLE_FIRST_FRAME, rf.RF_SAMPLE_EQUAL_INTERVAL):
         hc, rec = rf.rf_arm_classify(Q, K, rl, rp, mode, 0.5)
         hc, rec = hc.cpu().numpy(), rec.cpu().numpy()
+        near = []
         for (b, h), (q, k, v) in heads.items():
             c, (rh, rt) = orc.arm_classify(q, k, ol, op, mode, 0.5)
-            assert abs(rec[b, h, 0] - rh) <= 1e-3 and abs(rec[b, h, 1] - rt) <= 1e-3, (b, h, rec[b, h], rh, rt)
-            if abs(rh - 0.5) >= 1e-3 and abs(rt - 0.5) >= 1e-3:
-                assert hc[b, h] == c, (b, h, hc[b, h], c, rh, rt)
+            check_arm_head((b, h), hc[b, h], rec[b, h], c, rh, rt, 0.5, near)
+        print("%s text-first mode %d: heads within 1e-3 of the threshold (exempt): %s" % (name, mode, near), flush=True)
 
 
 def test_force_dense_flag_ignores_the_classes():
@@ -190,6 +190,17 @@ def test_force_dense_flag_ignores_the_classes():
 
 
 # ----------------------------------------------------------------------------- ARM
+def check_arm_head(what, got_class, got_recalls, want_class, rh, rt, alpha, near):
+    """Recalls within 1e-3 of the oracle's; the class exact unless the recall that DECIDES it (Alg. 1:
+    R-hat, or R-tilde once R-hat is below the threshold) lies within 1e-3 of the threshold; such heads
+    are appended to `near` (the caller prints them) and exempt."""
+    assert abs(got_recalls[0] - rh) <= 1e-3 and abs(got_recalls[1] - rt) <= 1e-3, (what, got_recalls, rh, rt)
+    if abs(rh - alpha) < 1e-3 or (rh < alpha and abs(rt - alpha) < 1e-3):
+        near.append((what, float(rh), float(rt)))
+        return
+    assert got_class == want_class, (what, got_class, want_class, rh, rt)
+
+
 def arm_compare(w, Q, K, mode, alpha, rparams, oparams, heads=None):
     rl, ol = lay(w)
     hc, rec = rf.rf_arm_classify(Q, K, rl, rparams, mode, alpha)
@@ -204,11 +215,7 @@ def arm_compare(w, Q, K, mode, alpha, rparams, oparams, heads=None):
                 continue
             q, k, _ = (f32(t) for t in inp.head_qkv(w, b, h))
             c, (rh, rt) = orc.arm_classify(q, k, ol, oparams, mode, alpha)
-            assert abs(rec[b, h, 0] - rh) <= 1e-3 and abs(rec[b, h, 1] - rt) <= 1e-3, (b, h, rec[b, h], rh, rt)
-            if abs(rh - alpha) < 1e-3 or abs(rt - alpha) < 1e-3:
-                near.append((b, h, rh, rt))
-                continue
-            assert hc[b, h] == c, (b, h, hc[b, h], c, rh, rt)
+            check_arm_head((b, h), hc[b, h], rec[b, h], c, rh, rt, alpha, near)
     print("%s mode %d alpha %g: heads within 1e-3 of the threshold (exempt): %s" % (w.name, mode, alpha, near),
           flush=True)
     return hc, rec
@@ -418,25 +425,40 @@ def test_step_replays_from_a_hip_graph():
                 check(O_graph[b, h], orc.attention(q, k, v, int(hc_graph[b, h]), ol), "graph replay %d head(%d,%d)" % (trial, b, h))
 
 
-def test_calls_on_two_streams_do_not_share_state():
-    """Two attention calls in flight at once on different streams (each with its own workspace) take
-    different work-queue counters; both must be right."""
+def test_many_calls_on_three_streams_and_a_replayed_graph():
+    """The work-queue counters live in each call's own workspace, so any number of calls may be in
+    flight: 72 launches over three streams (each stream with its own workspace and output) while a
+    captured graph with a fourth workspace is replayed in between; every output against the oracle."""
     w = inp.WORKLOADS["ragged96"]
-    print("case two streams", flush=True)
+    print("case many streams", flush=True)
     rl, ol = lay(w)
     Q, K, V = inp.full_qkv(w, DEV, 6.0)
-    classes = [torch.full((w.B, w.nH), c, dtype=torch.int32, device=DEV) for c in (rf.RF_TEMPORAL, rf.RF_TEXTURAL)]
-    wss = [torch.empty(rf.rf_attention_workspace_bytes(w.B, w.nH, w.D, rl, None), dtype=torch.uint8, device=DEV) for _ in range(2)]
-    outs = [torch.empty_like(Q) for _ in range(2)]
-    rf.rf_sparse_attention(Q, K, V, classes[0], rl, None, 64, out=outs[0], workspace=wss[0])  # lists built
+    kinds = (rf.RF_TEMPORAL, rf.RF_TEXTURAL, rf.RF_SPATIAL, rf.RF_DENSE)
+    classes = [torch.full((w.B, w.nH), c, dtype=torch.int32, device=DEV) for c in kinds]
+    full = rf.rf_attention_workspace_bytes(w.B, w.nH, w.D, rl, None)
+    # two full workspaces (packed copies), one with the counters only, one full for the graph
+    wss = [torch.empty(n, dtype=torch.uint8, device=DEV) for n in (full, rf.RF_ATTENTION_MIN_WORKSPACE, full, full)]
+    outs = [torch.empty_like(Q) for _ in range(4)]
+    blocks = (64, 128, 256, 128)
+    for i in range(4):  # lists built, kernel attributes set
+        rf.rf_sparse_attention(Q, K, V, classes[i], rl, None, blocks[i], out=outs[i], workspace=wss[i])
     torch.cuda.synchronize()
-    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
-    for rep in range(8):
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        rf.rf_sparse_attention(Q, K, V, classes[3], rl, None, blocks[3], out=outs[3], workspace=wss[3])
+    torch.cuda.synchronize()
+    for o in outs:
+        o.zero_()
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    for rep in range(24):
         for i, s in enumerate(streams):
             with torch.cuda.stream(s):
-                rf.rf_sparse_attention(Q, K, V, classes[i], rl, None, 64, out=outs[i], workspace=wss[i])
+                rf.rf_sparse_attention(Q, K, V, classes[i], rl, None, blocks[i], out=outs[i], workspace=wss[i])
+        if rep % 4 == 0:
+            graph.replay()
     torch.cuda.synchronize()
-    for i, cls in enumerate((rf.RF_TEMPORAL, rf.RF_TEXTURAL)):
+    for i, cls in enumerate(kinds):
         for h in range(w.nH):
             q, k, v = (f32(t) for t in inp.head_qkv(w, 0, h, 6.0))
             check(outs[i][0, h], orc.attention(q, k, v, cls, ol), "stream %d head %d" % (i, h))
@@ -515,13 +537,15 @@ def test_random_small_arm_configurations():
         hc, rec = hc.cpu().numpy(), rec.cpu().numpy()
         bws = [0.5, 0.125, 0.25]
         hcp, hbw, recp = (t.cpu().numpy() for t in rf.rf_arm_classify_plus(Q, K, rl, rp, mode, alpha, bws))
+        near = []
         for h in range(nH):
             q, k, _ = (np.roll(f32(t), shift, axis=0) for t in inp.head_qkv(w, 0, h, 3.0))
             c, (rh, rt) = orc.arm_classify(q, k, ol, op, mode, alpha)
-            assert abs(rec[0, h, 0] - rh) <= 1e-3 and abs(rec[0, h, 1] - rt) <= 1e-3, (case, h, rec[0, h], rh, rt)
-            if min(abs(rh - alpha), abs(rt - alpha)) >= 1e-3:
-                assert hc[0, h] == c, (case, h, hc[0, h], c, rh, rt)
+            check_arm_head((case, h), hc[0, h], rec[0, h], c, rh, rt, alpha, near)
             cp, idx, orec = orc.arm_classify_plus(q, k, ol, op, mode, alpha, bws)
             assert np.abs(recp[0, h] - orec).max() <= 1e-3, (case, h, recp[0, h], orec)
             if np.abs(orec - alpha).min() >= 1e-3:
                 assert (hcp[0, h], hbw[0, h]) == (cp, idx), (case, h, hcp[0, h], hbw[0, h], cp, idx)
+            else:
+                near.append(((case, h, "plus"), orec.round(4).tolist()))
+        print("random arm case %d: heads within 1e-3 of the threshold (exempt): %s" % (case, near), flush=True)

@@ -250,8 +250,15 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     assert attn(par=rf.rf_params(0.25, 0.25, 0, 0)) == -4 and attn(par=rf.rf_params(float("nan"), 0.25, 2, 0)) == -4
     assert attn(block=32) == -5 and attn(block=512) == -5 and attn(block=0) == -5
     need = rf.rf_attention_workspace_bytes(1, 2, 64, L)
-    assert need == 2 * 2 * 256 * 64 * 2  # a copy of K and of V: 2 heads x 256 tokens x 64 channels, bf16
-    assert attn(ws=C.c_void_p(256), wsb=need - 1) == -6 and attn(ws=C.c_void_p(264), wsb=need) == -6
+    # the work-queue counters, then a copy of K and of V: 2 heads x 256 tokens x 64 channels, bf16
+    assert need == rf.RF_ATTENTION_MIN_WORKSPACE + 2 * 2 * 256 * 64 * 2
+    # the workspace is required, holds at least the counters, and is 256-byte aligned
+    assert attn(ws=None) == -6 and attn(ws=C.c_void_p(256), wsb=rf.RF_ATTENTION_MIN_WORKSPACE - 1) == -6
+    assert attn(ws=C.c_void_p(264), wsb=need) == -8
+    # tensors are moved 16 bytes at a time
+    odd = C.c_void_p(24)
+    assert attn(Q=odd) == -8 and attn(K=odd) == -8 and attn(V=odd) == -8 and attn(O=odd) == -8
+    assert "align" in rf.rf_status_string(-8)
     assert rf.rf_attention_workspace_bytes(1, 2, 80, L) == 0
 
     def arm(Q=one, K=one, B=1, nH=2, D=64, lay=L, mode=0, thr=0.9, hc=one, ws=one, wsb=1 << 20):
@@ -262,6 +269,8 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     assert arm(D=32) == -2
     assert arm(mode=2) == -4 and arm(thr=1.5) == -4 and arm(thr=float("nan")) == -4
     assert arm(ws=None) == -6 and arm(wsb=8) == -6
+    assert arm(Q=C.c_void_p(8)) == -8 and arm(K=C.c_void_p(40)) == -8
+
     assert rf.rf_arm_workspace_bytes(1, 2, L) == 1 * 2 * 2 * 64 * 4
     assert rf.rf_arm_workspace_bytes(0, 2, L) == 0
     # per-head bandwidth variants: candidate list checked on the host before anything else
