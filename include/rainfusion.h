@@ -109,6 +109,23 @@ int rf_arm_classify(const void *Q, const void *K, int B, int nH, int D, const rf
 size_t rf_arm_workspace_bytes(int B, int nH, const rf_layout *layout, const rf_params *params);
 
 /*
+ * rf_arm_classify for callers that cannot allocate device memory or pass a workspace along (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments
+ * minus the workspace, same kernels, same results.  The per-row recalls go to a static array of
+ * RF_ARM_STATIC_SCRATCH_BYTES inside the library's device image instead (every GPU the library
+ * runs on holds one until the process ends).  The call allocates and frees nothing.
+ *   - Problems that need more scratch than that (rf_arm_workspace_bytes() > RF_ARM_STATIC_SCRATCH_BYTES)
+ *     are refused with RF_ERR_WORKSPACE before any GPU work.
+ *   - All calls on one GPU share the array: calls that overlap in time on one GPU (different
+ *     streams, or replays of graphs that captured it) race with each other.  Nothing in it has to
+ *     start at zero; its contents are undefined afterwards.
+ */
+#define RF_ARM_STATIC_SCRATCH_BYTES (2u << 20)
+int rf_arm_classify_noalloc(const void *Q, const void *K, int B, int nH, int D, const rf_layout *layout,
+                            const rf_params *params, int sample_mode, float threshold, int32_t *head_class,
+                            float *recalls, void *stream);
+
+/*
  * RainFusion+ (Sec. 4.3): ARM with per-head bandwidth.  Alg. 1's two recalls are measured once
  * per candidate bandwidth (bandwidths[k] replaces both bw_temporal and bw_spatial of `params`),
  * in the same pass over the sampled scores.  A head is TEMPORAL with the narrowest candidate

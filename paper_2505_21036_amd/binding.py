@@ -19,6 +19,7 @@ RF_PLAN_PARTIAL = 0x40000000
 RF_KEY_TILE = 64
 RF_LIST_TEMPORAL_POSITION_MAJOR = 4
 RF_ATTENTION_MIN_WORKSPACE = 256
+RF_ARM_STATIC_SCRATCH_BYTES = 2 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("RF_LIBRARY") or os.path.join(_HERE, "librainfusion.so")
@@ -67,6 +68,8 @@ def load_library():
     lib.rf_arm_classify.restype = C.c_int
     lib.rf_arm_classify.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, PL, PP, C.c_int, C.c_float, vp, vp, vp,
                                     C.c_size_t, vp]
+    lib.rf_arm_classify_noalloc.restype = C.c_int
+    lib.rf_arm_classify_noalloc.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, PL, PP, C.c_int, C.c_float, vp, vp, vp]
     lib.rf_sparse_attention.restype = C.c_int
     lib.rf_sparse_attention.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, PL, PP, C.c_int, vp, vp, C.c_size_t,
                                         vp]
@@ -142,6 +145,23 @@ def rf_arm_classify(Q, K, layout, params=None, sample_mode=RF_SAMPLE_FIRST_FRAME
                                         _stream())
     if st != 0:
         raise RfError(st, "rf_arm_classify")
+    return head_class, recalls
+
+
+def rf_arm_classify_noalloc(Q, K, layout, params, sample_mode, threshold, head_class, recalls):
+    """ARM (Alg. 1) without a workspace argument: per-row recalls go to the library's static scratch.
+    head_class (int32 [B, nH]) and recalls (float32 [B, nH, 2]) are device tensors the caller provides,
+    so the call allocates nothing."""
+    _check_bf16(Q, "Q")
+    _check_bf16(K, "K", Q.shape)
+    B, nH, N, D = Q.shape
+    if N != layout.T * layout.H * layout.W + layout.text_len:
+        raise ValueError("N does not match the layout")
+    st = load_library().rf_arm_classify_noalloc(Q.data_ptr(), K.data_ptr(), B, nH, D, C.byref(layout), _pp(params),
+                                                sample_mode, threshold, head_class.data_ptr(), recalls.data_ptr(),
+                                                _stream())
+    if st != 0:
+        raise RfError(st, "rf_arm_classify_noalloc")
     return head_class, recalls
 
 

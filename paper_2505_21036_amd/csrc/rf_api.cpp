@@ -258,6 +258,27 @@ int rf_arm_classify(const void* Q, const void* K, int B, int nH, int D, const rf
                              recalls, workspace, workspace_bytes, stream);
 }
 
+int rf_arm_classify_noalloc(const void* Q, const void* K, int B, int nH, int D, const rf_layout* layout,
+                            const rf_params* params, int sample_mode, float threshold, int32_t* head_class,
+                            float* recalls, void* stream) {
+    // every argument check, and the size limit, before any HIP call
+    if (!Q || !K || !head_class || !layout) return RF_ERR_NULL;
+    Geometry g;
+    int st = resolve_geometry(layout, params, &g);
+    if (st != RF_OK) return st;
+    st = check_shape(B, nH, D);
+    if (st != RF_OK) return st;
+    if (!aligned16(Q) || !aligned16(K)) return RF_ERR_ALIGN;
+    if (sample_mode != RF_SAMPLE_FIRST_FRAME && sample_mode != RF_SAMPLE_EQUAL_INTERVAL) return RF_ERR_PARAM;
+    if (!(threshold >= 0.f && threshold <= 1.f)) return RF_ERR_PARAM;
+    if (rf_arm_workspace_bytes(B, nH, layout, params) > kArmStaticScratchBytes) return RF_ERR_WORKSPACE;
+    void* scratch = nullptr;
+    size_t scratch_bytes = 0;
+    if (arm_static_scratch(&scratch, &scratch_bytes) != 0) return RF_ERR_HIP;
+    return arm_classify_impl(Q, K, B, nH, D, layout, params, sample_mode, threshold, nullptr, 1, head_class, nullptr,
+                             recalls, scratch, scratch_bytes, stream);
+}
+
 int rf_arm_classify_plus(const void* Q, const void* K, int B, int nH, int D, const rf_layout* layout,
                          const rf_params* params, int sample_mode, float threshold, const float* bandwidths,
                          int n_bw, int32_t* head_class, int32_t* head_bw, float* recalls, void* workspace,

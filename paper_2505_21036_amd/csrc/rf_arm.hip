@@ -13,6 +13,8 @@
 // A sample's attribute (in-frame position or frame) follows from its index by arithmetic; no table of
 // samples exists anywhere.  Per-row recalls go to scratch and are reduced in a fixed order by
 // arm_finish_kernel, which also applies the decision rule.
+#include <mutex>
+
 #include "rf_device.h"
 
 namespace rf {
@@ -262,6 +264,30 @@ static int launch_arm_d(const ArmArgs& a, hipStream_t st) {
     if (e != hipSuccess) return static_cast<int>(e);
     hipLaunchKernelGGL(arm_finish_kernel, dim3(a.BH), dim3(256), 0, st, a);
     return static_cast<int>(hipGetLastError());
+}
+
+// Scratch for callers that cannot allocate (rf_arm_classify_noalloc): lives in the library's image on
+// every GPU the library runs on, at an address that differs from device to device.
+static __device__ __align__(256) unsigned char scratch[kArmStaticScratchBytes];
+
+int arm_static_scratch(void** ptr, size_t* bytes) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* address[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return static_cast<int>(e);
+    if (dev < 0 || dev >= kMaxDevices) return static_cast<int>(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!address[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));  // with device `dev` current: that device's copy
+        if (e != hipSuccess) return static_cast<int>(e);
+        address[dev] = p;
+    }
+    *ptr = address[dev];
+    *bytes = kArmStaticScratchBytes;
+    return 0;
 }
 
 int launch_arm(const ArmArgs& a, int D, void* stream) {

@@ -137,5 +137,8 @@ struct ArmArgs {
 int launch_attention(const AttnArgs& a, int D, void* stream);
 int launch_pack_textural(const AttnArgs& a, int D, void* stream);
 int launch_arm(const ArmArgs& a, int D, void* stream);
+// Device address and size of the library's static scratch array on the current device (rf_arm.hip).
+int arm_static_scratch(void** ptr, size_t* bytes);
+constexpr size_t kArmStaticScratchBytes = RF_ARM_STATIC_SCRATCH_BYTES;
 
 }  // namespace rf

@@ -223,7 +223,7 @@ def test_every_declared_symbol_is_exported():
     names = re.findall(r"\b(rf_[a-z_]+)\s*\(", hdr)
     assert set(names) >= {"rf_arm_classify", "rf_sparse_attention", "rf_arm_workspace_bytes", "rf_plan_host",
                           "rf_attention_workspace_bytes", "rf_plan_order", "rf_arm_classify_plus",
-                          "rf_sparse_attention_plus", "rf_plan_position_major",
+                          "rf_sparse_attention_plus", "rf_plan_position_major", "rf_arm_classify_noalloc",
                           "rf_plan_clear", "rf_status_string", "rf_version"}
     for n in set(names):
         assert getattr(lib, n) is not None
@@ -271,6 +271,15 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     assert arm(ws=None) == -6 and arm(wsb=8) == -6
     assert arm(Q=C.c_void_p(8)) == -8 and arm(K=C.c_void_p(40)) == -8
 
+    # the variant without a workspace: same checks, and problems beyond its static scratch are refused
+    def armn(Q=one, K=one, B=1, nH=2, D=64, lay=L, mode=0, thr=0.9, hc=one):
+        return lib.rf_arm_classify_noalloc(Q, K, B, nH, D, C.byref(lay) if lay else None, None, mode, thr, hc, None, None)
+
+    assert armn(Q=None) == -1 and armn(hc=None) == -1 and armn(lay=None) == -1
+    assert armn(D=32) == -2 and armn(mode=2) == -4 and armn(thr=1.5) == -4 and armn(Q=C.c_void_p(8)) == -8
+    big_layout = rf.rf_layout(33, 45, 80, 256)  # 3600 sampled rows per pass
+    assert rf.rf_arm_workspace_bytes(24, 3, big_layout) <= rf.RF_ARM_STATIC_SCRATCH_BYTES < rf.rf_arm_workspace_bytes(25, 3, big_layout)
+    assert armn(B=25, nH=3, lay=big_layout) == -6
     assert rf.rf_arm_workspace_bytes(1, 2, L) == 1 * 2 * 2 * 64 * 4
     assert rf.rf_arm_workspace_bytes(0, 2, L) == 0
     # per-head bandwidth variants: candidate list checked on the host before anything else
