@@ -21,11 +21,12 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 
-# HBM-side bytes of one attention launch of the timed step (ARM-chosen classes), from the rocprofv3
-# --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/attn_kernel_hunyuan720p.md: counter
-# values in KiB, FETCH_SIZE scaled x2.0 and WRITE_SIZE x1.0 (what the same counters read for a
-# 1 GiB device copy).  Only known for the workload / block it was profiled on.
-MEASURED_TRAFFIC_BYTES = {("hunyuan720p", 256): (2.0 * 1.8893e7 + 1.0 * 7.147e5) * 1024}
+# HBM-side bytes of one attention launch of the timed step (ARM-chosen classes).  NOT observed by
+# this script: copied from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/attn_kernel_hunyuan720p.md (counter values in KiB, FETCH_SIZE scaled x2.0 and WRITE_SIZE
+# x1.0, what the same counters read for a 1 GiB device copy).  Only known for the workload / block
+# it was profiled on; the bench line says where the figure comes from.
+PROFILED_TRAFFIC_BYTES = {("hunyuan720p", 256): (2.0 * 1.8893e7 + 1.0 * 7.147e5) * 1024}
 
 
 def kept_pairs(cls, w, bw_s=0.25, bw_t=0.25, tau=2):
@@ -54,7 +55,7 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="hunyuan720p")
-    ap.add_argument("--block", type=int, default=0, help="skip-list block (64|128); 0 = the workload's")
+    ap.add_argument("--block", type=int, default=0, help="query rows per block (64|128|256); 0 = the workload's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the step: time the bandwidth / stride settings of the paper's sensitivity "
@@ -62,6 +63,11 @@ def main():
     ap.add_argument("--plus", action="store_true",
                     help="instead of the step: time RainFusion+ (per-head bandwidth from 0.5/0.25/0.125) on the "
                          "planted workload, whose heads the ARM can tell apart; prints one JSON line")
+    ap.add_argument("--configs", action="store_true",
+                    help="instead of the step: the other named configurations, each against the same kernel run dense: "
+                         "the CogVideoX-shaped layer with round-robin classes and with ARM-chosen classes (equal-interval "
+                         "sampling), the Open-Sora-Plan-shaped layer at blocks 128 and 256, the planted layer at blocks "
+                         "64 and 128 with ARM-chosen classes; prints one JSON line")
     ap.add_argument("--only", default="", help="profiling aid: run just 'step', 'arm', 'thirds', 'dense', every head 'spatial' / 'temporal' / 'textural', or 'copy' (a 1 GiB device copy)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -74,6 +80,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
+    if args.configs:
+        args.workload = "tiny"  # --configs brings its own workloads; keep the common set-up below small
     w = inp.WORKLOADS[args.workload]
     block = args.block or w.block
     rl = rf.rf_layout(w.T, w.H, w.W, w.text_len)
@@ -157,6 +165,56 @@ def main():
         print(json.dumps({"plus": res}))
         return
 
+    if args.configs:
+        del Q, K, V, O, ws_attn
+        torch.cuda.empty_cache()
+        rows = []
+
+        def time_config(name, blocks, arm_mode=None, forced=None):
+            wc = inp.WORKLOADS[name]
+            rlc = rf.rf_layout(wc.T, wc.H, wc.W, wc.text_len)
+            Qc, Kc, Vc = inp.full_qkv(wc, dev)
+            Oc = torch.empty_like(Qc)
+            wsc = torch.empty(rf.rf_attention_workspace_bytes(wc.B, wc.nH, wc.D, rlc), dtype=torch.uint8, device=dev)
+            densec = torch.full((wc.B, wc.nH), rf.RF_DENSE, dtype=torch.int32, device=dev)
+            row = {"workload": "%s: B%d nH%d D%d, %d frames x %dx%d + %d text = %d tokens" % (
+                wc.name, wc.B, wc.nH, wc.D, wc.T, wc.H, wc.W, wc.text_len, wc.N)}
+            if arm_mode is not None:
+                hcc, _ = rf.rf_arm_classify(Qc, Kc, rlc, None, arm_mode, 0.9)
+                row["classes"] = "chosen by the ARM (%s sampling)" % ("first-frame", "equal-interval")[arm_mode]
+                armf = lambda: rf.rf_arm_classify(Qc, Kc, rlc, None, arm_mode, 0.9)
+                armf()
+                row["arm_ms"] = round(event_ms(armf, 5), 4)
+            else:
+                hcc = forced(wc).to(dev)
+                row["classes"] = forced.__name__
+            ch = hcc.cpu().flatten().tolist()
+            row["class_histogram"] = {"spatial": ch.count(0), "temporal": ch.count(1), "textural": ch.count(2), "dense": ch.count(3)}
+            kept = sum(kept_pairs(c, wc) for c in ch) / float(wc.B * wc.nH * wc.N * wc.N)
+            row["kept_fraction"] = round(kept, 4)
+            for blk in blocks:
+                sparse = lambda: rf.rf_sparse_attention(Qc, Kc, Vc, hcc, rlc, None, blk, Oc, wsc)
+                densef = lambda: rf.rf_sparse_attention(Qc, Kc, Vc, densec, rlc, None, blk, Oc, wsc)
+                sparse()
+                ms = event_ms(sparse, 5)
+                densef()
+                msd = event_ms(densef, 3)
+                row["block_%d" % blk] = {"sparse_ms": round(ms, 4), "dense_ms": round(msd, 4), "speedup_vs_dense": round(msd / ms, 3),
+                                         "flop_count_speedup": round(1 / kept, 3),
+                                         "tflops_useful": round(kept * wc.dense_flops() / ms / 1e9, 1),
+                                         "tflops_dense": round(wc.dense_flops() / msd / 1e9, 1),
+                                         "mfma_frac_dense": round(wc.dense_flops() / msd / 1e9 / PEAK_BF16_TFLOPS, 4)}
+                if "arm_ms" in row:
+                    row["block_%d" % blk]["arm_pct_of_sparse_attention"] = round(100 * row["arm_ms"] / ms, 3)
+            rows.append(row)
+
+        time_config("cogvideox", (128, 256), forced=inp.round_robin_classes)
+        time_config("cogvideox", (128, 256), arm_mode=rf.RF_SAMPLE_EQUAL_INTERVAL)
+        time_config("osp720p", (128, 256), forced=inp.thirds_classes)
+        time_config("planted", (64, 128), arm_mode=rf.RF_SAMPLE_FIRST_FRAME)
+        print(json.dumps({"configs": rows}))
+        return
+
     if args.only:
         one = {n: torch.full((w.B, w.nH), c, dtype=torch.int32, device=dev)
                for n, c in (("spatial", rf.RF_SPATIAL), ("temporal", rf.RF_TEMPORAL), ("textural", rf.RF_TEXTURAL))}
@@ -202,6 +260,43 @@ def main():
     ms_thirds = event_ms(lambda: attn(thirds), reps)
     attn(dense)
     ms_dense = event_ms(lambda: attn(dense), max(2, reps // 2))
+
+    # ---- the same step on planted heads of the same shape, where the ARM picks all three patterns
+    planted = None
+    wp = inp.WORKLOADS.get(w.name + "_planted")
+    if wp is not None:
+        Qp, Kp, Vp = inp.full_qkv(wp, dev)
+
+        def planted_step():
+            rf.rf_arm_classify(Qp, Kp, rl, None, rf.RF_SAMPLE_FIRST_FRAME, 0.9, hc, rec, ws)
+            rf.rf_sparse_attention(Qp, Kp, Vp, hc, rl, None, block, O, ws_attn)
+
+        planted_step()
+        torch.cuda.synchronize()
+        evp = []
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            rf.rf_arm_classify(Qp, Kp, rl, None, rf.RF_SAMPLE_FIRST_FRAME, 0.9, hc, rec, ws)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            rf.rf_sparse_attention(Qp, Kp, Vp, hc, rl, None, block, O, ws_attn)
+            b.record()
+            evp.append((a, b))
+        torch.cuda.synchronize()
+        ms_planted_step = (time.perf_counter() - t0) * 1e3 / reps
+        ms_planted_attn = sum(a.elapsed_time(b) for a, b in evp) / reps
+        pc = hc.cpu().flatten().tolist()
+        want = [inp.planted_class(wp, b, h) for b in range(wp.B) for h in range(wp.nH)]
+        useful_p = 4.0 * w.D * sum(kept_pairs(c, w) for c in pc)
+        planted = {"planted_step_ms": round(ms_planted_step, 4), "planted_attention_ms": round(ms_planted_attn, 4),
+                   "planted_arm_classes": {"spatial": pc.count(0), "temporal": pc.count(1), "textural": pc.count(2)},
+                   "planted_classes_recovered": pc == want,
+                   "planted_useful_flop_fraction": round(useful_p / w.dense_flops(), 4),
+                   "planted_tflops_useful": round(useful_p / ms_planted_attn / 1e9, 2),
+                   "planted_mfma_frac_useful": round(useful_p / ms_planted_attn / 1e9 / PEAK_BF16_TFLOPS, 4),
+                   "planted_speedup_vs_dense": round(ms_dense / ms_planted_attn, 3)}
+        del Qp, Kp, Vp
+        arm()  # leave the i.i.d. classes in hc again
 
     # ---- FLOP bookkeeping: 4*D flops per (query, key) pair for QK^T and PV
     per_pair = 4.0 * w.D
@@ -251,7 +346,13 @@ def main():
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(useful_arm / ms_attn_arm_classes / 1e9 / PEAK_BF16_TFLOPS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, block)),
+            "traffic": PROFILED_TRAFFIC_BYTES.get((w.name, block)),
+            "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run recorded in profiles/attn_kernel_hunyuan720p.md; "
+                              "not observed by this run",
+            "traffic_gbps_at_this_runs_time": (round(PROFILED_TRAFFIC_BYTES[(w.name, block)] / ms_attn_arm_classes / 1e6, 1)
+                                               if (w.name, block) in PROFILED_TRAFFIC_BYTES else None),
+            "algorithmic_bytes": 8.0 * w.N * w.D * w.nH * w.B,
+            "algorithmic_gbps": round(8.0 * w.N * w.D * w.nH * w.B / ms_attn_arm_classes / 1e6, 1),
         },
         "detail": {
             "attention_ms_arm_classes": round(ms_attn_arm_classes, 4),
@@ -275,6 +376,8 @@ def main():
             "paper_context": "paper reports 1.84-1.91x attention speedup (hardware not stated), ARM ~0.2 %",
         },
     }
+    if planted:
+        out["detail"].update(planted)
 
     if not args.no_cpu_baseline:
         import numpy as np

@@ -61,6 +61,9 @@ WORKLOADS = {
     # planted-structure ARM validation
     "planted": Workload("planted", 2, 16, 128, 16, 32, 32, 0, 128, 1005,
                         planted=(SPATIAL, TEMPORAL, TEXTURAL)),
+    # the headline shape with planted heads, so that the ARM picks all three patterns there
+    "hunyuan720p_planted": Workload("hunyuan720p_planted", 1, 24, 128, 33, 45, 80, 256, 256, 1009,
+                                    planted=(SPATIAL, TEMPORAL, TEXTURAL)),
     # small ragged shapes for parity sweeps: frames not block aligned, ragged tail, text
     "ragged64": Workload("ragged64", 1, 3, 64, 5, 6, 11, 19, 64, 1006),
     "ragged96": Workload("ragged96", 1, 3, 96, 6, 9, 10, 37, 128, 1007),
@@ -84,8 +87,9 @@ def head_qkv(w: Workload, b: int, h: int, scale: float = 1.0):
 
     i.i.d. workloads: N(0,1)/sqrt(D) (times ``scale`` on Q, to make the softmax peaky).
     Planted workloads: q_n = k_n = g * R[:, code(n)] + N(0, 0.1^2), V ~ N(0,1), where R
-    is a seeded random orthogonal matrix and code(n) is the frame (Spatial), the
-    16-token in-frame group (Temporal) or the in-frame index mod 64 (Textural).
+    is a seeded random orthogonal matrix and code(n) is the frame (Spatial), the in-frame
+    group of consecutive positions (Temporal; groups of 16, or as many as it takes for the
+    number of groups to fit D) or the in-frame index mod 64 (Textural).
     """
     N, D = w.N, w.D
     if not w.planted:
@@ -99,7 +103,7 @@ def head_qkv(w: Workload, b: int, h: int, scale: float = 1.0):
     if cls == SPATIAL:
         code = f
     elif cls == TEMPORAL:
-        code = p // 16
+        code = p // max(16, -(-w.HW // D))
     else:
         code = p % 64
     assert int(code.max()) < D

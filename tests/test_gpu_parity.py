@@ -4,7 +4,8 @@ on sampled rows the oracle computes one by one, plus properties that hold at any
 
 Tolerances (bf16 inputs, fp32 accumulation, bf16 output): max-abs 2e-2 and mean-abs 2e-3, the
 contract for this path.  Because i.i.d. inputs give outputs of only ~1e-2..1e-3 in size, the
-relative L2 error is asserted as well (1.5e-2), and peaky / planted inputs with O(1) outputs
+relative L2 error is asserted as well: 5.2e-3, twice the largest value any case of this suite
+prints (2.6e-3, the bf16 rounding of P and of O); peaky and planted inputs with larger outputs
 are included.  ARM: recalls within 1e-3; classes exact unless a recall lies within 1e-3 of the
 threshold (those heads are printed and exempt).
 """
@@ -20,7 +21,7 @@ import rf_inputs as inp
 
 pytestmark = pytest.mark.gpu
 
-MAX_ABS, MEAN_ABS, REL_L2 = 2e-2, 2e-3, 1.5e-2
+MAX_ABS, MEAN_ABS, REL_L2 = 2e-2, 2e-3, 5.2e-3
 DEV = "cuda:0"
 
 
@@ -313,6 +314,38 @@ def test_plus_planted_structure_gets_the_narrowest_band():
             assert hbw[b, h] == (-1 if cls == rf.RF_TEXTURAL else 2), (b, h, rec[b, h])
 
 
+@pytest.mark.parametrize("text_first", [False, True])
+def test_plus_attention_with_a_workspace_and_two_bandwidths_per_pattern(text_first):
+    """rf_sparse_attention_plus with the full workspace: Temporal heads walk position-major copies with
+    the list of THEIR bandwidth, Textural heads the packed K_C/V_C; heads of one pattern at different
+    bandwidths in one call, text tokens behind or in front."""
+    w = inp.WORKLOADS["ragged128"]
+    print("case plus workspace", text_first, flush=True)
+    rl, ol = lay(w)
+    tl, scale = w.text_len, 5.0
+    shift = tl if text_first else 0
+    rp = rf.rf_params(0.25, 0.25, 2, 0, rf.RF_FLAG_TEXT_FIRST if text_first else 0)
+    Q, K, V = (torch.roll(t, shift, dims=2).contiguous() for t in inp.full_qkv(w, DEV, scale))
+    bws = [0.5, 0.25, 0.125]
+    classes = [rf.RF_TEMPORAL, rf.RF_TEMPORAL, rf.RF_SPATIAL, rf.RF_SPATIAL, rf.RF_TEXTURAL, rf.RF_TEMPORAL]
+    chosen = [0, 2, 1, 2, -1, 1]
+    hc = torch.as_tensor(classes, dtype=torch.int32).reshape(w.B, w.nH).to(DEV)
+    hbw = torch.as_tensor(chosen, dtype=torch.int32).reshape(w.B, w.nH).to(DEV)
+    ws = torch.empty(rf.rf_attention_workspace_bytes(w.B, w.nH, w.D, rl, rp), dtype=torch.uint8, device=DEV)
+    for block in (64, 128, 256):
+        for workspace in (ws, None):
+            O = rf.rf_sparse_attention_plus(Q, K, V, hc, hbw, bws, rl, rp, block, workspace=workspace)
+            torch.cuda.synchronize()
+            for b in range(w.B):
+                for h in range(w.nH):
+                    i = b * w.nH + h
+                    bw = bws[chosen[i]] if chosen[i] >= 0 else 0.25
+                    q, k, v = (np.roll(f32(t), shift, axis=0) for t in inp.head_qkv(w, b, h, scale))
+                    ref = orc.attention(q, k, v, classes[i], ol, orc.Params(bw, bw, 2, 0, False, text_first))
+                    check(O[b, h], ref, "plus ws%d text-first%d blk%d head(%d,%d) cls%d bw%g" % (
+                        workspace is not None, text_first, block, b, h, classes[i], bw))
+
+
 # ----------------------------------------------------------------------------- paper-sized layers
 def sampled_parity(w, O, classes, heads, per_head, params=orc.Params(), tag=""):
     _, ol = lay(w)
@@ -348,6 +381,8 @@ def test_osp720p_layer_sparse_and_dense():
     classes = inp.thirds_classes(w).flatten().tolist()
     O = run_attention(w, Q, K, V, classes, w.block)
     sampled_parity(w, O, classes, [(0, 0), (0, 9), (0, 23)], 20, tag="thirds")
+    O = run_attention(w, Q, K, V, classes, 128, packed=True)  # the block size the configuration names
+    sampled_parity(w, O, classes, [(0, 1), (0, 10), (0, 22)], 20, tag="thirds, packed, block 128")
     dense = [rf.RF_DENSE] * w.nH
     O = run_attention(w, Q, K, V, dense, w.block)
     sampled_parity(w, O, dense, [(0, 11)], 12, tag="dense")
@@ -374,6 +409,25 @@ def test_hunyuan720p_headline_layer():
     # property at full size: constant values must come back as that constant on every row
     O = run_attention(w, Q, K, torch.ones_like(V), classes, w.block)
     assert (O.float() - 1).abs().max().item() <= 1e-2
+
+
+def test_hunyuan720p_planted_layer_arm_picks_all_three_patterns():
+    """The headline shape with planted heads: the ARM must return the planted class for every head
+    (Alg. 1 -> Eq. 3-5 on the device, all three list walks in one launch), equal to the oracle's on two
+    heads per class, and the attention with those classes, run as bench.py runs it, must match the
+    oracle on sampled rows."""
+    w = inp.WORKLOADS["hunyuan720p_planted"]
+    print("case hunyuan720p planted", flush=True)
+    Q, K, V = inp.full_qkv(w, DEV)
+    heads = [(0, 0), (0, 1), (0, 2), (0, 9), (0, 16), (0, 23)]
+    hc, rec = arm_compare(w, Q, K, rf.RF_SAMPLE_FIRST_FRAME, 0.9, *par(), heads=set(heads))
+    for h in range(w.nH):
+        assert hc[0, h] == inp.planted_class(w, 0, h), (h, rec[0, h])
+    classes = hc.flatten().tolist()
+    O = run_attention(w, Q, K, V, classes, w.block, packed=True)
+    sampled_parity(w, O, classes, heads, 16, tag="planted, arm-chosen, packed")
+    O = run_attention(w, Q, K, V, classes, 128)
+    sampled_parity(w, O, classes, [(0, 3), (0, 4), (0, 5)], 16, tag="planted, arm-chosen, block 128, no copies")
 
 
 # ----------------------------------------------------------------------------- graphs and streams
