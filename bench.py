@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--workload", default="hunyuan720p")
     ap.add_argument("--block", type=int, default=0, help="query rows per block (64|128|256); 0 = the workload's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fixed-order", action="store_true",
+                    help="run the attention with RF_FLAG_FIXED_ORDER (bitwise reproducible tile order)")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the step: time the bandwidth / stride settings of the paper's sensitivity "
                          "table (w = 0.25/0.18/0.13, tau = 2/3/4) against the dense run; prints one JSON line")
@@ -97,8 +99,10 @@ def main():
     def arm():
         rf.rf_arm_classify(Q, K, rl, None, rf.RF_SAMPLE_FIRST_FRAME, 0.9, hc, rec, ws)
 
+    attn_params = rf.rf_params(0.25, 0.25, 2, 0, rf.RF_FLAG_FIXED_ORDER) if args.fixed_order else None
+
     def attn(classes):
-        rf.rf_sparse_attention(Q, K, V, classes, rl, None, block, O, ws_attn)
+        rf.rf_sparse_attention(Q, K, V, classes, rl, attn_params, block, O, ws_attn)
 
     def step():
         arm()

@@ -16,8 +16,8 @@
  *     default stream) and never synchronise it, except that the first call for a new
  *     (layout, params, block) builds and uploads its block lists synchronously.  After
  *     such a warm-up call a sequence of calls only launches kernels (no memsets, no
- *     allocations) and can be captured into a HIP graph; results are bitwise the same
- *     from call to call.  All per-call device state lives in the caller's workspaces, so
+ *     allocations) and can be captured into a HIP graph; the ARM's results are bitwise the
+ *     same from call to call, the attention's under RF_FLAG_FIXED_ORDER.  All per-call device state lives in the caller's workspaces, so
  *     any number of calls may be in flight as long as each has its own workspace.  The
  *     library keeps at most 16 block lists per process (least recently used first out;
  *     making room synchronises the device).
@@ -67,6 +67,13 @@ typedef struct {
  * NULL): the "first 10 % of the timesteps dense" policy of Sec. 4.1 without touching the class
  * buffer.  Ignored by the ARM. */
 #define RF_FLAG_FORCE_DENSE 4
+/* rf_sparse_attention visits each query block's key tiles in an order fixed by the layout alone, which
+ * makes O bitwise identical from call to call.  Without the flag a query block starts its (cyclic) walk
+ * over its tiles wherever the workgroups already running on the same part of the GPU are, so that they
+ * share K/V tiles through the L2 cache: every tile is still visited exactly once, but the fp32 sums are
+ * formed in an order that depends on timing, so the last bit of O can differ between calls (faster,
+ * chiefly on Spatial and Temporal heads).  Ignored by the ARM, whose results are always reproducible. */
+#define RF_FLAG_FIXED_ORDER 8
 
 #define RF_MAX_BANDWIDTHS 4 /* candidate bandwidths of the per-head bandwidth variant */
 
@@ -164,7 +171,7 @@ int rf_arm_classify_plus(const void *Q, const void *K, int B, int nH, int D, con
  *               contiguous run of keys per query block.  The result is the same either way.  Contents
  *               undefined afterwards; calls that overlap in time need separate workspaces.
  */
-#define RF_ATTENTION_MIN_WORKSPACE 256
+#define RF_ATTENTION_MIN_WORKSPACE 512
 int rf_sparse_attention(const void *Q, const void *K, const void *V, const int32_t *head_class, int B,
                         int nH, int D, const rf_layout *layout, const rf_params *params, int block,
                         void *O, void *workspace, size_t workspace_bytes, void *stream);

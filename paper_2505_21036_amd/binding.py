@@ -15,10 +15,11 @@ RF_SAMPLE_FIRST_FRAME, RF_SAMPLE_EQUAL_INTERVAL = 0, 1
 RF_FLAG_TWO_HEAD = 1
 RF_FLAG_TEXT_FIRST = 2
 RF_FLAG_FORCE_DENSE = 4
+RF_FLAG_FIXED_ORDER = 8
 RF_PLAN_PARTIAL = 0x40000000
 RF_KEY_TILE = 64
 RF_LIST_TEMPORAL_POSITION_MAJOR = 4
-RF_ATTENTION_MIN_WORKSPACE = 256
+RF_ATTENTION_MIN_WORKSPACE = 512
 RF_ARM_STATIC_SCRATCH_BYTES = 2 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

@@ -332,6 +332,7 @@ static int sparse_attention_impl(const void* Q, const void* K, const void* V, co
     a.V = static_cast<const uint16_t*>(V);
     a.O = static_cast<uint16_t*>(O);
     a.queue = static_cast<int*>(workspace);
+    a.join_sweep = (params && (params->flags & RF_FLAG_FIXED_ORDER)) ? 0 : 1;
     a.head_class = force_dense ? nullptr : head_class;
     a.head_bw = bandwidths ? head_bw : nullptr;
     a.BH = B * nH;

@@ -53,10 +53,25 @@ struct QueryBlock {
     // tokens come first in the tensors, and 0 when kbase/vbase are packed copies (already in walked order)
     int video_shift, text_shift;
     const int32_t* cols;  // MODE_LISTED: this query block's tile entries
-    int first;            // MODE_LISTED: entry the (cyclic) walk starts at
+    int first;            // entry (tile, for the unlisted walks) the cyclic walk starts at
     int ntiles;           // key tiles to visit
+    int* sweep;           // null, or: where this workgroup publishes how far its walk has come (see join_sweep)
+    int sweep_tag;        // which key sequence the published tile index refers to
     int keyN;             // length of the key sequence walked (N, or Nc when compacted)
 };
+
+// Workgroups of one XCD share that XCD's L2, so they should walk the same key tiles at the same time.
+// Items are handed out one by one as workgroups finish, so a workgroup that starts an item finds the
+// others somewhere in the middle of theirs: it joins them.  Every workgroup publishes, every few
+// tiles, the tile its walk has reached (with a tag naming the head and the key sequence) in one of
+// kSweepSlots words per XCD next to the work-queue counters (an XCD is usually on two or three heads
+// at a time: the slot is the head's index modulo kSweepSlots); a starting workgroup whose item walks
+// the same sequence begins its cyclic walk at that tile if the tile is in its list.  This only moves
+// where the walk starts: every tile of the list is still visited exactly once.
+constexpr int kSweepTileBits = 18, kSweepTileMask = (1 << kSweepTileBits) - 1;  // N <= 2^24 tokens: tile indices below 2^18
+constexpr int kSweepSlots = 8, kQueueWords = 8 + 8 * kSweepSlots;
+static_assert(kQueueWords * 4 <= RF_ATTENTION_MIN_WORKSPACE, "counters and sweep words live in the minimum workspace");
+__device__ __forceinline__ int* sweep_word(int* queue, int xcd, int bh) { return queue + 8 + xcd * kSweepSlots + (bh & (kSweepSlots - 1)); }
 
 // exp2 arguments may exceed 0 by at most this much before the running reference is moved: the
 // softmax is invariant to the reference, so a stale one only costs range, which fp32/bf16 have.
@@ -130,7 +145,9 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
             }
             return __builtin_amdgcn_readlane(ent_cur, t - ent_base);
         }
-        return t | ((t + 1) * kTileK > keyN ? (RF_PLAN_PARTIAL | kTileBoundary) : 0);
+        int tile = t + qk.first;  // the walk starts at tile qk.first and wraps
+        if (tile >= ntiles) tile -= ntiles;
+        return tile | ((tile + 1) * kTileK > keyN ? (RF_PLAN_PARTIAL | kTileBoundary) : 0);
     };
     // side data is needed for every tile of the compacted sequence, and for partial listed tiles
     auto wants_side = [&](int entry) { return MODE == MODE_COMPACT || (MODE == MODE_LISTED && (entry & RF_PLAN_PARTIAL)); };
@@ -250,6 +267,9 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
         if (t + AHEAD < ntiles) fetch_tile(t + AHEAD, e[AHEAD]);
         if (t + DEPTH < ntiles) load_side(e[DEPTH]);
         const int e_cur = e[0];
+        // every eighth tile, tell the workgroups that start an item on this XCD where this walk is
+        if (qk.sweep && (t & 7) == 0 && tid == 0)
+            __hip_atomic_store(qk.sweep, (qk.sweep_tag << kSweepTileBits) | (e_cur & kSweepTileMask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
         // Online softmax (Eq. 1) in base 2 with 1/sqrt(D) folded into c.  The reference subtracted in
         // the exponent is moved, and the accumulators rescaled, only when a row outgrows it by more
@@ -371,11 +391,18 @@ __device__ __forceinline__ int take_item(int* ctr, int home, const Queues& qs, i
     }
 }
 
-template <int D, int NW>
-__device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xcd, const Queues& qs, unsigned char* smem);
+// head of the item-th item of queue xcd (see Queues)
+__device__ __forceinline__ int item_head(int item, int xcd, const Queues& qs) {
+    const int longs = qs.long_items(xcd);
+    return item < longs ? (item * 8 + xcd) / qs.nTB : (item - longs) / qs.share(xcd);
+}
 
+template <int D, int NW>
+__device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xcd, int seen, const Queues& qs, unsigned char* smem);
+
+// Eight queue counters, then the sweep words (-1: nothing published yet).
 __global__ void reset_queue_kernel(int* ctr) {
-    if (threadIdx.x < 8) ctr[threadIdx.x] = 0;
+    if (threadIdx.x < kQueueWords) ctr[threadIdx.x] = threadIdx.x < 8 ? 0 : -1;
 }
 
 template <int D, int NW>
@@ -399,19 +426,27 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
             int q = 0;
             item_box[0] = take_item(a.queue, blockIdx.x & 7, qs, &q);
             item_box[1] = q;
+            // the sweep word for the item's head on this workgroup's XCD (it serves its own L2, whichever queue
+            // the item came from), read ONCE for the whole workgroup: it changes all the time
+            const int it = item_box[0];
+            item_box[2] = (a.join_sweep && it >= 0)
+                              ? __hip_atomic_load(sweep_word(a.queue, blockIdx.x & 7, item_head(it, q, qs)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                              : -1;
         }
         __syncthreads();
         // wavefront-uniform by construction; say so, so that everything derived stays in scalar registers
         const int item = __builtin_amdgcn_readfirstlane(item_box[0]), xcd = __builtin_amdgcn_readfirstlane(item_box[1]);
+        const int seen = __builtin_amdgcn_readfirstlane(item_box[2]);
         __syncthreads();
         if (item < 0) break;
-        process_item<D, NW>(a, item, xcd, qs, smem);
+        process_item<D, NW>(a, item, xcd, seen, qs, smem);
     }
 }
 
-// One (head, query block) item: item-th of queue xcd.
+// One (head, query block) item: item-th of queue xcd.  seen: the sweep word of this workgroup's XCD
+// (it serves its own L2, whichever queue the item came from), or -1.
 template <int D, int NW>
-__device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xcd, const Queues& qs, unsigned char* smem) {
+__device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xcd, int seen, const Queues& qs, unsigned char* smem) {
     // position in the block order, and the head
     int ordinal, bh;
     const int longs = qs.long_items(xcd);
@@ -443,6 +478,8 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xc
     qk.qb = cls == RF_DENSE ? (ordinal < qs.nTB ? qs.nVB + ordinal : ordinal - qs.nTB) : pl.qorder[list][ordinal];
     qk.first = 0;
     qk.cols = nullptr;
+    qk.sweep = a.join_sweep ? sweep_word(a.queue, blockIdx.x & 7, bh) : nullptr;
+    auto same_sequence = [&]() { return seen >= 0 && (seen >> kSweepTileBits) == qk.sweep_tag; };
     qk.list = cls;
     qk.row_token = nullptr;
     qk.video_shift = pl.video_shift;
@@ -450,9 +487,14 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xc
     const size_t head_bytes = static_cast<size_t>(qk.bh) * pl.N * D * 2;
     qk.kbase = reinterpret_cast<const unsigned char*>(a.K) + head_bytes;
     qk.vbase = reinterpret_cast<const unsigned char*>(a.V) + head_bytes;
+    // tag: the head and which of its key sequences is walked (token order, compacted, position-major)
+    const int kTagBits = 31 - kSweepTileBits;
+    auto tag_of = [&](int sequence) { return (qk.bh * 4 + sequence) & ((1 << kTagBits) - 1); };
     if (cls == RF_DENSE) {
         qk.ntiles = pl.nKT;
         qk.keyN = pl.N;
+        qk.sweep_tag = tag_of(0);
+        if (same_sequence() && (seen & kSweepTileMask) < qk.ntiles) qk.first = seen & kSweepTileMask;
         attend<D, NW, MODE_ALL>(a, pl, qk, smem);
     } else if (cls == RF_TEXTURAL && qk.qb < pl.first_text_qb) {
         // Textural query blocks made only of video tokens see the compacted key sequence (Eq. 5):
@@ -460,6 +502,8 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xc
         // gathered row by row through the index table
         qk.ntiles = pl.nCT;
         qk.keyN = pl.Nc;
+        qk.sweep_tag = tag_of(1);
+        if (same_sequence() && (seen & kSweepTileMask) < qk.ntiles) qk.first = seen & kSweepTileMask;
         if (a.packed_k) {
             const size_t packed_bytes = head_bytes;
             qk.kbase = reinterpret_cast<const unsigned char*>(a.packed_k) + packed_bytes;
@@ -482,6 +526,15 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xc
         qk.cols = pl.cols[list] + e0;
         qk.first = pl.first_entry[list][qk.qb];
         qk.keyN = pl.N;
+        qk.sweep_tag = tag_of(temporal_pm ? 2 : 0);
+        if (same_sequence() && qk.ntiles > 0) {
+            // banded lists are one run of consecutive tiles (then the text tiles): the published tile,
+            // if it is in the run, sits at entry (tile - first tile of the run)
+            const int tile = seen & kSweepTileMask, at = tile - (qk.cols[0] & kTileIndexMask);
+            // if it is not (the others are just outside this block's band, which overlaps theirs almost
+            // entirely), the start of the run is where they will be next
+            qk.first = (at >= 0 && at < qk.ntiles && (qk.cols[at] & kTileIndexMask) == tile) ? at : 0;
+        }
         attend<D, NW, MODE_LISTED>(a, pl, qk, smem);
     }
 }

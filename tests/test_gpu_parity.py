@@ -445,9 +445,11 @@ def test_step_replays_from_a_hip_graph():
     rec = torch.empty(w.B, w.nH, 2, dtype=torch.float32, device=DEV)
     O = torch.empty_like(Q)
 
+    fixed = rf.rf_params(0.25, 0.25, 2, 0, rf.RF_FLAG_FIXED_ORDER)  # bitwise reproducible attention
+
     def step():
         rf.rf_arm_classify(Q, K, rl, None, rf.RF_SAMPLE_FIRST_FRAME, 0.45, hc, rec, arm_ws)
-        rf.rf_sparse_attention(Q, K, V, hc, rl, None, 128, out=O, workspace=ws)
+        rf.rf_sparse_attention(Q, K, V, hc, rl, fixed, 128, out=O, workspace=ws)
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
