@@ -20,7 +20,7 @@
  * Readings taken where the paper is silent or garbled (each also listed in the
  * design notes of the repository):
  *   - Spatial: query frame f attends every token of frames f' with
- *     |f - f'| <= floor(bw_spatial * T)  ("neighbouring frames", band over frames);
+ *     |f - f'| <= floor(bw_spatial * T)  (a band over frames: the frames next to f);
  *   - Temporal: with p the index of a token inside its frame, query p attends
  *     p' with |p - p'| <= floor(bw_temporal * H*W) in every frame (local inside
  *     a frame sub-sequence, periodic over the sequence);
@@ -32,7 +32,7 @@
  *   - Eq. 6 is read per query row: recall = mean over sampled rows of the
  *     softmax mass that falls on kept sampled keys;
  *   - global sampling interval omega defaults to T (|sample| ~= H*W, the
- *     "1/t^2 overhead" of Sec. 1);
+ *     overhead falling with the square of the frame count that Sec. 1 states);
  *   - ">=" at the threshold, Temporal tested first (Alg. 1).
  */
 #include <math.h>
@@ -283,8 +283,8 @@ int rfo_arm_classify(const float *Q, const float *K, int D, const rfo_layout *L,
 }
 
 /*
- * RainFusion+ (Sec. 4.3, "dynamic bandwidth selection (0.5, 0.25, 0.125) across different
- * attention heads ... the minimum value that maintains 90% recall"), one head.  The recalls of
+ * RainFusion+ (Sec. 4.3: every head gets the narrowest of the candidate bandwidths 0.5, 0.25,
+ * 0.125 whose recall still reaches 90 %), one head.  The recalls of
  * Alg. 1 are evaluated once per candidate bandwidth bws[k] (the Temporal recall with
  * bw_temporal = bws[k], the Spatial recall with bw_spatial = bws[k]).  Reading taken: Alg. 1's
  * order is kept -- if any candidate gives R-hat >= alpha the head is Temporal with the smallest
