@@ -53,7 +53,7 @@ WORKLOADS = {
     # tiny oracle case
     "tiny": Workload("tiny", 1, 2, 64, 4, 8, 8, 0, 64, 1001),
     # CogVideoX-5B-shaped layer, 226 text tokens
-    "cogvideox": Workload("cogvideox", 1, 48, 64, 13, 30, 45, 226, 128, 1002),
+    "cogvideox": Workload("cogvideox", 1, 48, 64, 13, 30, 45, 226, 256, 1002),
     # Open-Sora-Plan-1.2 720p-shaped layer
     "osp720p": Workload("osp720p", 1, 24, 96, 24, 45, 80, 0, 256, 1003),
     # HunyuanVideo 720p-shaped layer, 256 text tokens (headline)
