@@ -19,36 +19,42 @@
 
 namespace rf {
 
-#ifndef RF_ARM_WAVES
-#define RF_ARM_WAVES 8
-#endif
-constexpr int kArmWaves = RF_ARM_WAVES;  // 32 sampled queries per wavefront
+// Wavefronts per workgroup, 32 sampled queries each.  A workgroup walks all sampled keys, so the
+// launch has (samples / 32 / waves) workgroups per head and pass: 8 waves when the passes run apart,
+// 4 when one workgroup serves both (half as many items, each twice as long: the finer grain keeps
+// the 256 CUs evenly loaded).
+constexpr int kArmWavesApart = 8, kArmWavesBoth = 4;
 // as in the attention kernel: the reference in the exponent moves only when a row outgrows it by this
 constexpr float kArmRescaleSlack = 8.f;
 
-template <int D>
+template <int D, int NW>
 struct ArmSmem {
-    using ST = DirectTile<D, kArmWaves>;
+    using ST = DirectTile<D, NW>;
     static constexpr int K_OFF = 0;                      // two K' tiles
-    static constexpr int ATTR_OFF = 2 * ST::K_BYTES;     // per tile: the 64 samples' attributes, then bounds on them (lowest, highest)
+    static constexpr int ATTR_OFF = 2 * ST::K_BYTES;     // per tile and pass: the 64 samples' attributes, then bounds on them (lowest, highest)
     static constexpr int ATTR_SLOT = kTileK + 2;
-    static constexpr int BYTES = ATTR_OFF + 2 * ATTR_SLOT * 4 + 16;
+    static constexpr int BYTES = ATTR_OFF + 2 * 2 * ATTR_SLOT * 4 + 16;
     static_assert(ST::K_BYTES % 256 == 0, "tile buffers must start at multiples of 256 bytes (see DirectTile::k_address)");
 };
 
-template <int D>
-__global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, int nQB) {
-    constexpr int NW = kArmWaves, BQ = 32 * NW;
-    using SM = ArmSmem<D>;
+// BOTH: the two passes use the same sample (equal-interval sampling), so one workgroup forms each
+// score tile once and keeps the kept-key sums of both masks; the arithmetic per pass, and so every
+// recall, is the same as when the passes run apart.
+template <int D, bool BOTH>
+__global__ void __launch_bounds__(64 * (BOTH ? kArmWavesBoth : kArmWavesApart)) arm_recall_kernel(ArmArgs a, int nQB) {
+    constexpr int NW = BOTH ? kArmWavesBoth : kArmWavesApart, BQ = 32 * NW, NP = BOTH ? 2 : 1;
+    using SM = ArmSmem<D, NW>;
     using ST = typename SM::ST;
     extern __shared__ __attribute__((aligned(256))) unsigned char smem[];  // the kernel's only LDS: starts at address 0
     int* abuf = reinterpret_cast<int*>(smem + SM::ATTR_OFF);
 
-    const int item = xcd_contiguous_item(blockIdx.x, nQB * 2 * a.BH);
+    const int item = xcd_contiguous_item(blockIdx.x, nQB * (2 / NP) * a.BH);
     if (item < 0) return;
-    const int qb = item % nQB, pass = (item / nQB) & 1, bh = item / (2 * nQB);
-    const ArmPass ps = a.pass[pass];
-    const int n = ps.n;
+    const int qb = item % nQB, pass0 = BOTH ? 0 : (item / nQB) & 1, bh = item / ((2 / NP) * nQB);
+    ArmPass ps[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) ps[i] = a.pass[pass0 + i];
+    const int n = ps[0].n, stride = ps[0].stride;  // BOTH: the same in the two passes (the host checks)
     if (qb * BQ >= n) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, m = lane & 31;
 
@@ -60,28 +66,35 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
     const int qs = qb * BQ + wave * 32 + m;  // this lane's sampled query
     const int qsc = min(qs, n - 1);
     bf16x8 qf[D / 16];
-    load_q_frags<D>(Qh, qsc * ps.stride, hf, qf);
-    auto attr_of = [&](int sample) {
-        const int token = sample * ps.stride;
-        return ps.by_frame ? token / ps.HW : token % ps.HW;
+    load_q_frags<D>(Qh, qsc * stride, hf, qf);
+    auto attr_of = [&](int i, int sample) {
+        const int token = sample * stride;
+        return ps[i].by_frame ? token / ps[i].HW : token % ps[i].HW;
     };
-    const int q_attr = attr_of(qsc);
-    // attribute range of this wavefront's 32 queries (both halves hold the same queries)
-    int q_min = q_attr, q_max = q_attr;
+    // attribute of this lane's query and its range over the wavefront's 32 queries (both halves hold
+    // the same queries)
+    int q_attr[NP], q_min[NP], q_max[NP];
 #pragma unroll
-    for (int w = 1; w < 32; w <<= 1) {
-        q_min = min(q_min, __shfl_xor(q_min, w, 64));
-        q_max = max(q_max, __shfl_xor(q_max, w, 64));
+    for (int i = 0; i < NP; ++i) {
+        q_attr[i] = attr_of(i, qsc);
+        int lo = q_attr[i], hi = q_attr[i];
+#pragma unroll
+        for (int w = 1; w < 32; w <<= 1) {
+            lo = min(lo, __shfl_xor(lo, w, 64));
+            hi = max(hi, __shfl_xor(hi, w, 64));
+        }
+        q_min[i] = __builtin_amdgcn_readfirstlane(lo);
+        q_max[i] = __builtin_amdgcn_readfirstlane(hi);
     }
-    q_min = __builtin_amdgcn_readfirstlane(q_min);
-    q_max = __builtin_amdgcn_readfirstlane(q_max);
 
     // m_ref: reference subtracted inside exp2 (raw score units); l_all / l_kept: this lane's share of
     // the denominator over all sampled keys and over the kept ones, both relative to m_ref
-    float m_ref = 0.f, l_all = 0.f, l_kept[kMaxBw];
+    float m_ref = 0.f, l_all = 0.f, l_kept[NP][kMaxBw];
     bool has_ref = false;
 #pragma unroll
-    for (int b = 0; b < kMaxBw; ++b) l_kept[b] = 0.f;
+    for (int i = 0; i < NP; ++i)
+#pragma unroll
+        for (int b = 0; b < kMaxBw; ++b) l_kept[i][b] = 0.f;
     const int n_bw = a.n_bw;
     const float c = a.scale_log2;
     const int ntiles = (n + kTileK - 1) / kTileK;
@@ -89,32 +102,39 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
     ST st;
     st.init(tid);
     auto k_lds = [&](int t) { return smem + SM::K_OFF + (t & 1) * ST::K_BYTES; };
-    int attr_reg = 0;
+    auto attr_slot = [&](int t, int i) { return abuf + ((t & 1) * 2 + i) * SM::ATTR_SLOT; };
+    int attr_reg[NP] = {};
     auto fetch_tile = [&](int t) {
         const int k0 = t * kTileK;
-        if (ps.stride == 1 && k0 + kTileK <= n)
+        if (stride == 1 && k0 + kTileK <= n)
             st.template issue_consecutive<false>(Kh + static_cast<size_t>(k0) * (2 * D), nullptr, k_lds(t), nullptr);
         else
-            st.template issue<false>(Kh, nullptr, k_lds(t), nullptr, [&](int r) { return min(k0 + r, n - 1) * ps.stride; });
+            st.template issue<false>(Kh, nullptr, k_lds(t), nullptr, [&](int r) { return min(k0 + r, n - 1) * stride; });
         // the tile's attributes (first wavefront, one sample per lane)
-        if (tid < kTileK) attr_reg = attr_of(min(k0 + tid, n - 1));
+        if (tid < kTileK) {
+#pragma unroll
+            for (int i = 0; i < NP; ++i) attr_reg[i] = attr_of(i, min(k0 + tid, n - 1));
+        }
     };
     // Also bounds on the tile's attributes: samples are in token order, so frames never decrease, and
     // positions do not either as long as the tile stays inside one frame; a tile that crosses into
     // another frame gets the widest bounds (the caller then masks it entry by entry, which is exact).
     auto stash_attr = [&](int t) {
         if (tid >= kTileK) return;
-        int* slot = abuf + (t & 1) * SM::ATTR_SLOT;
-        slot[tid] = attr_reg;
-        const int first = t * kTileK * ps.stride, last = min(t * kTileK + kTileK - 1, n - 1) * ps.stride;
-        int lo = __builtin_amdgcn_readlane(attr_reg, 0), hi = __builtin_amdgcn_readlane(attr_reg, kTileK - 1);
-        if (!ps.by_frame && first / ps.HW != last / ps.HW) {
-            lo = 0;
-            hi = ps.HW - 1;
-        }
-        if (tid == 0) {
-            slot[kTileK] = lo;
-            slot[kTileK + 1] = hi;
+        const int first = t * kTileK * stride, last = min(t * kTileK + kTileK - 1, n - 1) * stride;
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            int* slot = attr_slot(t, i);
+            slot[tid] = attr_reg[i];
+            int lo = __builtin_amdgcn_readlane(attr_reg[i], 0), hi = __builtin_amdgcn_readlane(attr_reg[i], kTileK - 1);
+            if (!ps[i].by_frame && first / ps[i].HW != last / ps[i].HW) {
+                lo = 0;
+                hi = ps[i].HW - 1;
+            }
+            if (tid == 0) {
+                slot[kTileK] = lo;
+                slot[kTileK + 1] = hi;
+            }
         }
     };
     fetch_tile(0);
@@ -127,7 +147,6 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
 
     for (int t = 0; t < ntiles; ++t) {
         if (t + 1 < ntiles) fetch_tile(t + 1);
-        const int* al = abuf + (t & 1) * SM::ATTR_SLOT;
         const int k0 = t * kTileK;
 
         f32x16 s[2];
@@ -154,53 +173,63 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
                 const float alpha = has_ref ? fast_exp2((m_ref - m_new) * c) : 0.f;  // nothing accumulated before
                 l_all *= alpha;
 #pragma unroll
-                for (int b = 0; b < kMaxBw; ++b) l_kept[b] *= alpha;
+                for (int i = 0; i < NP; ++i)
+#pragma unroll
+                    for (int b = 0; b < kMaxBw; ++b) l_kept[i][b] *= alpha;
                 m_ref = m_new;
                 has_ref = true;
             }
         }
         const float mc = m_ref * c;
-        float sum_all = 0.f, sum_kept[kMaxBw];
+        // the tile's terms of the denominator, summed in register order whatever the masks need
+        float sum_all = 0.f;
 #pragma unroll
-        for (int b = 0; b < kMaxBw; ++b) sum_kept[b] = 0.f;
-        // Where does the band's edge fall for this (wavefront, tile) pair?  inside: bit b set if every
-        // pair is within radius b; mixed: some candidate has both kept and dropped pairs here.
-        const int k_min = __builtin_amdgcn_readfirstlane(al[kTileK]), k_max = __builtin_amdgcn_readfirstlane(al[kTileK + 1]);
-        const int reach = max(k_max - q_min, q_max - k_min), gap = max(k_min - q_max, q_min - k_max);
-        int inside = 0;
-        bool mixed = false;
+        for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
-        for (int b = 0; b < kMaxBw; ++b) {
-            if (b >= n_bw) break;
-            if (reach <= ps.radius[b]) inside |= 1 << b;
-            else if (gap <= ps.radius[b]) mixed = true;
-        }
-        if (!mixed) {
-#pragma unroll
-            for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sum_all += fast_exp2(fmaf(s[kb2][r], c, -mc));
-#pragma unroll
-            for (int b = 0; b < kMaxBw; ++b) sum_kept[b] = ((inside >> b) & 1) ? sum_all : 0.f;
-        } else {
-#pragma unroll
-            for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float p = fast_exp2(fmaf(s[kb2][r], c, -mc));
-                    const int d = q_attr - al[32 * kb2 + key_of_reg(r, hf)];
-                    const int dist = d < 0 ? -d : d;
-                    sum_all += p;
-                    sum_kept[0] += dist <= ps.radius[0] ? p : 0.f;
-                    if (n_bw > 1) {  // uniform: the per-head bandwidth variant measures every candidate at once
-#pragma unroll
-                        for (int b = 1; b < kMaxBw; ++b) sum_kept[b] += (b < n_bw && dist <= ps.radius[b]) ? p : 0.f;
-                    }
-                }
-        }
+            for (int r = 0; r < 16; ++r) {
+                s[kb2][r] = fast_exp2(fmaf(s[kb2][r], c, -mc));
+                sum_all += s[kb2][r];
+            }
         l_all += sum_all;
 #pragma unroll
-        for (int b = 0; b < kMaxBw; ++b) l_kept[b] += sum_kept[b];
+        for (int i = 0; i < NP; ++i) {
+            // Where does the band's edge fall for this (wavefront, tile) pair?  inside: bit b set if every
+            // pair is within radius b; mixed: some candidate has both kept and dropped pairs here.
+            const int* al = attr_slot(t, i);
+            const int k_min = __builtin_amdgcn_readfirstlane(al[kTileK]), k_max = __builtin_amdgcn_readfirstlane(al[kTileK + 1]);
+            const int reach = max(k_max - q_min[i], q_max[i] - k_min), gap = max(k_min - q_max[i], q_min[i] - k_max);
+            int inside = 0;
+            bool mixed = false;
+#pragma unroll
+            for (int b = 0; b < kMaxBw; ++b) {
+                if (b >= n_bw) break;
+                if (reach <= ps[i].radius[b]) inside |= 1 << b;
+                else if (gap <= ps[i].radius[b]) mixed = true;
+            }
+            if (!mixed) {
+#pragma unroll
+                for (int b = 0; b < kMaxBw; ++b) l_kept[i][b] += ((inside >> b) & 1) ? sum_all : 0.f;
+            } else {
+                float sum_kept[kMaxBw];
+#pragma unroll
+                for (int b = 0; b < kMaxBw; ++b) sum_kept[b] = 0.f;
+#pragma unroll
+                for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float p = s[kb2][r];
+                        const int d = q_attr[i] - al[32 * kb2 + key_of_reg(r, hf)];
+                        const int dist = d < 0 ? -d : d;
+                        sum_kept[0] += dist <= ps[i].radius[0] ? p : 0.f;
+                        if (n_bw > 1) {  // uniform: the per-head bandwidth variant measures every candidate at once
+#pragma unroll
+                            for (int b = 1; b < kMaxBw; ++b) sum_kept[b] += (b < n_bw && dist <= ps[i].radius[b]) ? p : 0.f;
+                        }
+                    }
+#pragma unroll
+                for (int b = 0; b < kMaxBw; ++b) l_kept[i][b] += sum_kept[b];
+            }
+        }
 
         if (t + 1 < ntiles) stash_attr(t + 1);
         ST::template wait_landed<0>();
@@ -208,12 +237,14 @@ __global__ void __launch_bounds__(64 * kArmWaves) arm_recall_kernel(ArmArgs a, i
     }
     l_all += other_half(l_all);
 #pragma unroll
-    for (int b = 0; b < kMaxBw; ++b) {
-        if (b >= n_bw) break;
-        const float kept = l_kept[b] + other_half(l_kept[b]);
-        if (hf == 0 && qs < n)
-            a.row_recall[((static_cast<size_t>(bh) * 2 + pass) * n_bw + b) * a.max_n + qs] = kept / l_all;  // Eq. 6, one row
-    }
+    for (int i = 0; i < NP; ++i)
+#pragma unroll
+        for (int b = 0; b < kMaxBw; ++b) {
+            if (b >= n_bw) break;
+            const float kept = l_kept[i][b] + other_half(l_kept[i][b]);
+            if (hf == 0 && qs < n)
+                a.row_recall[((static_cast<size_t>(bh) * 2 + pass0 + i) * n_bw + b) * a.max_n + qs] = kept / l_all;  // Eq. 6, one row
+        }
 }
 
 // Mean of the per-row recalls in a fixed summation order, then Alg. 1's rule (with several
@@ -257,9 +288,16 @@ __global__ void __launch_bounds__(256) arm_finish_kernel(ArmArgs a) {
 
 template <int D>
 static int launch_arm_d(const ArmArgs& a, hipStream_t st) {
-    const int nQB = (a.max_n + 32 * kArmWaves - 1) / (32 * kArmWaves);
-    const int total = nQB * 2 * a.BH;
-    hipLaunchKernelGGL((arm_recall_kernel<D>), dim3(8 * ((total + 7) / 8)), dim3(64 * kArmWaves), ArmSmem<D>::BYTES, st, a, nQB);
+    const bool both = a.pass[0].n == a.pass[1].n && a.pass[0].stride == a.pass[1].stride;  // one sample for the two passes
+    const int NW = both ? kArmWavesBoth : kArmWavesApart;
+    const int nQB = (a.max_n + 32 * NW - 1) / (32 * NW);
+    const int total = nQB * (both ? 1 : 2) * a.BH;
+    const dim3 grid(8 * ((total + 7) / 8)), block(64 * NW);
+    constexpr int lds_both = ArmSmem<D, kArmWavesBoth>::BYTES, lds_apart = ArmSmem<D, kArmWavesApart>::BYTES;
+    if (both)
+        hipLaunchKernelGGL((arm_recall_kernel<D, true>), grid, block, lds_both, st, a, nQB);
+    else
+        hipLaunchKernelGGL((arm_recall_kernel<D, false>), grid, block, lds_apart, st, a, nQB);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return static_cast<int>(e);
     hipLaunchKernelGGL(arm_finish_kernel, dim3(a.BH), dim3(256), 0, st, a);
