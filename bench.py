@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--workload", default="hunyuan720p")
     ap.add_argument("--block", type=int, default=0, help="query rows per block (64|128|256); 0 = the workload's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--wide-rows", action="store_true",
+                    help="run the attention with RF_FLAG_WIDE_ROWS (64 query rows per wavefront; head_dim 128, block 256)")
     ap.add_argument("--fixed-order", action="store_true",
                     help="run the attention with RF_FLAG_FIXED_ORDER (bitwise reproducible tile order)")
     ap.add_argument("--sweep", action="store_true",
@@ -99,7 +101,8 @@ def main():
     def arm():
         rf.rf_arm_classify(Q, K, rl, None, rf.RF_SAMPLE_FIRST_FRAME, 0.9, hc, rec, ws)
 
-    attn_params = rf.rf_params(0.25, 0.25, 2, 0, rf.RF_FLAG_FIXED_ORDER) if args.fixed_order else None
+    attn_flags = (rf.RF_FLAG_FIXED_ORDER if args.fixed_order else 0) | (rf.RF_FLAG_WIDE_ROWS if args.wide_rows else 0)
+    attn_params = rf.rf_params(0.25, 0.25, 2, 0, attn_flags) if attn_flags else None
 
     def attn(classes):
         rf.rf_sparse_attention(Q, K, V, classes, rl, attn_params, block, O, ws_attn)

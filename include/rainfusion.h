@@ -74,6 +74,11 @@ typedef struct {
  * formed in an order that depends on timing, so the last bit of O can differ between calls (faster,
  * chiefly on Spatial and Temporal heads).  Ignored by the ARM, whose results are always reproducible. */
 #define RF_FLAG_FIXED_ORDER 8
+/* rf_sparse_attention runs the variant of its kernel in which a wavefront owns 64 query rows instead
+ * of 32 (half the shared-memory operand reads per matrix instruction, one wavefront per SIMD, the
+ * softmax of one tile interleaved with the matrix instructions of its neighbours).  Same result to
+ * rounding order.  Only with head_dim 128 and block 256 (RF_ERR_PARAM otherwise).  Ignored by the ARM. */
+#define RF_FLAG_WIDE_ROWS 16
 
 #define RF_MAX_BANDWIDTHS 4 /* candidate bandwidths of the per-head bandwidth variant */
 

@@ -16,6 +16,7 @@ RF_FLAG_TWO_HEAD = 1
 RF_FLAG_TEXT_FIRST = 2
 RF_FLAG_FORCE_DENSE = 4
 RF_FLAG_FIXED_ORDER = 8
+RF_FLAG_WIDE_ROWS = 16
 RF_PLAN_PARTIAL = 0x40000000
 RF_KEY_TILE = 64
 RF_LIST_TEMPORAL_POSITION_MAJOR = 4

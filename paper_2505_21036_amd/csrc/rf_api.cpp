@@ -309,6 +309,7 @@ static int sparse_attention_impl(const void* Q, const void* K, const void* V, co
     st = check_shape(B, nH, D);
     if (st != RF_OK) return st;
     if (!valid_block(block)) return RF_ERR_BLOCK;
+    if (params && (params->flags & RF_FLAG_WIDE_ROWS) && (block != 256 || D != 128)) return RF_ERR_PARAM;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return RF_ERR_ALIGN;
     // the work-queue counters live in the first RF_ATTENTION_MIN_WORKSPACE bytes; a workspace of the
     // full size also has room for the packed copies of K and V
@@ -333,6 +334,7 @@ static int sparse_attention_impl(const void* Q, const void* K, const void* V, co
     a.O = static_cast<uint16_t*>(O);
     a.queue = static_cast<int*>(workspace);
     a.join_sweep = (params && (params->flags & RF_FLAG_FIXED_ORDER)) ? 0 : 1;
+    a.wide_rows = (params && (params->flags & RF_FLAG_WIDE_ROWS)) ? 1 : 0;
     a.head_class = force_dense ? nullptr : head_class;
     a.head_bw = bandwidths ? head_bw : nullptr;
     a.BH = B * nH;

@@ -9,6 +9,7 @@
 // score.
 #include <algorithm>
 #include <mutex>
+#include <type_traits>
 
 #include "rf_device.h"
 
@@ -77,6 +78,11 @@ __device__ __forceinline__ int* sweep_word(int* queue, int xcd, int bh) { return
 // softmax is invariant to the reference, so a stale one only costs range, which fp32/bf16 have.
 constexpr float kRescaleSlack = 8.f;
 
+}  // namespace rf
+
+#include "rf_attn_wide.h"
+
+namespace rf {
 
 template <int D, int NW, int MODE>
 __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, const QueryBlock& qk, unsigned char* smem) {
@@ -349,8 +355,12 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
 }
 
 // Wavefronts per SIMD the register allocation is held to: three for head_dim 64 with 128-row
-// blocks (measured best; its accumulators are half the size), two otherwise.
-constexpr int attn_waves_per_simd(int D, int NW) { return (D == 64 && NW == 4) ? 3 : 2; }  // NW = 8: one workgroup per CU
+// blocks (measured best; its accumulators are half the size), two otherwise; one for wavefronts of
+// 64 query rows (WIDE), which need the whole register file.
+constexpr int attn_waves_per_simd(int D, int NW, bool WIDE) { return WIDE ? 1 : (D == 64 && NW == 4) ? 3 : 2; }  // NW = 8: one workgroup per CU
+
+template <int D, int NW, bool WIDE>
+using SmemOf = std::conditional_t<WIDE, WideSmem<D, NW>, AttnSmem<D, NW>>;
 
 // Items of one launch.  Queue x holds first its share of the long items (the nTB text-holding blocks
 // of every head: global index i = head * nTB + k goes to queue i mod 8), then, head after head, the
@@ -397,7 +407,7 @@ __device__ __forceinline__ int item_head(int item, int xcd, const Queues& qs) {
     return item < longs ? (item * 8 + xcd) / qs.nTB : (item - longs) / qs.share(xcd);
 }
 
-template <int D, int NW>
+template <int D, int NW, bool WIDE>
 __device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xcd, int seen, const Queues& qs, unsigned char* smem);
 
 // Eight queue counters, then the sweep words (-1: nothing published yet).
@@ -405,10 +415,11 @@ __global__ void reset_queue_kernel(int* ctr) {
     if (threadIdx.x < kQueueWords) ctr[threadIdx.x] = threadIdx.x < 8 ? 0 : -1;
 }
 
-template <int D, int NW>
-__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(attn_waves_per_simd(D, NW), attn_waves_per_simd(D, NW)))) attn_kernel(AttnArgs a) {
+// NW wavefronts of 32 query rows each, or (WIDE) of 64.
+template <int D, int NW, bool WIDE>
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(attn_waves_per_simd(D, NW, WIDE), attn_waves_per_simd(D, NW, WIDE)))) attn_kernel(AttnArgs a) {
     extern __shared__ __attribute__((aligned(256))) unsigned char smem[];  // the kernel's only LDS: starts at address 0
-    int* item_box = reinterpret_cast<int*>(smem + AttnSmem<D, NW>::ITEM_OFF);
+    int* item_box = reinterpret_cast<int*>(smem + SmemOf<D, NW, WIDE>::ITEM_OFF);
     // A resident set of workgroups (as many as fit on the chip) works through the (head, query
     // block) items.  Workgroup ids go to the 8 XCDs round-robin; XCD x's queue is one eighth of every
     // head's block order, head after head (neighbours in that order walk nearly the same key tiles,
@@ -439,14 +450,19 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
         const int seen = __builtin_amdgcn_readfirstlane(item_box[2]);
         __syncthreads();
         if (item < 0) break;
-        process_item<D, NW>(a, item, xcd, seen, qs, smem);
+        process_item<D, NW, WIDE>(a, item, xcd, seen, qs, smem);
     }
 }
 
 // One (head, query block) item: item-th of queue xcd.  seen: the sweep word of this workgroup's XCD
 // (it serves its own L2, whichever queue the item came from), or -1.
-template <int D, int NW>
+template <int D, int NW, bool WIDE>
 __device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xcd, int seen, const Queues& qs, unsigned char* smem) {
+    auto run = [&](auto mode, const DevicePlan& plan, const QueryBlock& block) {
+        constexpr int MODE = decltype(mode)::value;
+        if constexpr (WIDE) attend_wide<D, NW, MODE>(a, plan, block, smem);
+        else attend<D, NW, MODE>(a, plan, block, smem);
+    };
     // position in the block order, and the head
     int ordinal, bh;
     const int longs = qs.long_items(xcd);
@@ -495,7 +511,7 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xc
         qk.keyN = pl.N;
         qk.sweep_tag = tag_of(0);
         if (same_sequence() && (seen & kSweepTileMask) < qk.ntiles) qk.first = seen & kSweepTileMask;
-        attend<D, NW, MODE_ALL>(a, pl, qk, smem);
+        run(std::integral_constant<int, MODE_ALL>{}, pl, qk);
     } else if (cls == RF_TEXTURAL && qk.qb < pl.first_text_qb) {
         // Textural query blocks made only of video tokens see the compacted key sequence (Eq. 5):
         // as a packed copy made by pack_textural_kernel if the caller gave room for one, else
@@ -509,9 +525,9 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xc
             qk.kbase = reinterpret_cast<const unsigned char*>(a.packed_k) + packed_bytes;
             qk.vbase = reinterpret_cast<const unsigned char*>(a.packed_v) + packed_bytes;
             qk.video_shift = qk.text_shift = 0;
-            attend<D, NW, MODE_ALL>(a, pl, qk, smem);
+            run(std::integral_constant<int, MODE_ALL>{}, pl, qk);
         } else {
-            attend<D, NW, MODE_COMPACT>(a, pl, qk, smem);
+            run(std::integral_constant<int, MODE_COMPACT>{}, pl, qk);
         }
     } else {
         qk.list = list;
@@ -535,7 +551,7 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xc
             // entirely), the start of the run is where they will be next
             qk.first = (at >= 0 && at < qk.ntiles && (qk.cols[at] & kTileIndexMask) == tile) ? at : 0;
         }
-        attend<D, NW, MODE_LISTED>(a, pl, qk, smem);
+        run(std::integral_constant<int, MODE_LISTED>{}, pl, qk);
     }
 }
 
@@ -571,10 +587,10 @@ int launch_pack_textural(const AttnArgs& a, int D, void* stream) {
     return static_cast<int>(hipGetLastError());
 }
 
-template <int D, int NW>
+template <int D, int NW, bool WIDE = false>
 static int launch_one(const AttnArgs& a, hipStream_t st) {
     constexpr int NT = 64 * NW;
-    constexpr int smem = AttnSmem<D, NW>::BYTES;
+    constexpr int smem = SmemOf<D, NW, WIDE>::BYTES;
     // workgroups each device holds at once, found on first use there (which also raises the kernel's dynamic-LDS limit)
     constexpr int kMaxDevices = 64;
     static std::mutex mu;
@@ -587,12 +603,12 @@ static int launch_one(const AttnArgs& a, hipStream_t st) {
     {
         std::lock_guard<std::mutex> lock(mu);
         if (resident_on[dev] == 0) {
-            const void* fn = reinterpret_cast<const void*>(&attn_kernel<D, NW>);
+            const void* fn = reinterpret_cast<const void*>(&attn_kernel<D, NW, WIDE>);
             e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
             if (e != hipSuccess) return static_cast<int>(e);
             int cus = 0, per_cu = 0;
             if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return static_cast<int>(e);
-            if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_kernel<D, NW>, NT, smem)) != hipSuccess)
+            if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_kernel<D, NW, WIDE>, NT, smem)) != hipSuccess)
                 return static_cast<int>(e);
             if (cus < 1 || per_cu < 1) return static_cast<int>(hipErrorInvalidValue);
             resident_on[dev] = cus * per_cu;
@@ -604,13 +620,18 @@ static int launch_one(const AttnArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(reset_queue_kernel, dim3(1), dim3(64), 0, st, a.queue);
     e = hipGetLastError();
     if (e != hipSuccess) return static_cast<int>(e);
-    hipLaunchKernelGGL((attn_kernel<D, NW>), dim3(grid), dim3(NT), smem, st, a);
+    hipLaunchKernelGGL((attn_kernel<D, NW, WIDE>), dim3(grid), dim3(NT), smem, st, a);
     return static_cast<int>(hipGetLastError());
 }
 
 int launch_attention(const AttnArgs& a, int D, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int nw = a.plan[0].block / 32;
+    if (a.wide_rows) {  // 64 query rows per wavefront: 256-row blocks as four wavefronts
+        if (nw != 8) return static_cast<int>(hipErrorInvalidValue);
+        if (D == 128) return launch_one<128, 4, true>(a, st);
+        return static_cast<int>(hipErrorInvalidValue);
+    }
     if (D == 64 && nw == 2) return launch_one<64, 2>(a, st);
     if (D == 64 && nw == 4) return launch_one<64, 4>(a, st);
     if (D == 96 && nw == 2) return launch_one<96, 2>(a, st);

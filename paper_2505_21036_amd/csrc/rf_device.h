@@ -175,8 +175,9 @@ struct DirectTile {
     }
 
     // tok(row): token whose K/V row goes to tile row `row`; kh/vh: byte pointers the tokens index.
-    // WITH_V = false: K only (the ARM needs no V).
-    template <bool WITH_V = true, typename F>
+    // WITH_V = false: K only (the ARM needs no V); WITH_K = false: V only (the attention loop for 64-row
+    // wavefronts loads the K and V of different tiles).
+    template <bool WITH_V = true, bool WITH_K = true, typename F>
     __device__ __forceinline__ void issue(const unsigned char* kh, const unsigned char* vh, unsigned char* kl,
                                           unsigned char* vl, F tok) {
 #pragma unroll
@@ -185,22 +186,24 @@ struct DirectTile {
             if (!EVEN && seg >= SEGS) break;
             const int slot = seg * 64 + lane, row = slot / CH, pos = slot % CH;
             const uint32_t row_off = static_cast<uint32_t>(tok(row)) * ROW;
-            dma16(kh, row_off + 16u * k_chunk(row, pos), lds_offset(kl) + seg * 1024);
+            if (WITH_K) dma16(kh, row_off + 16u * k_chunk(row, pos), lds_offset(kl) + seg * 1024);
             if (WITH_V) dma16(vh, row_off + 16u * v_slot(row, pos), lds_offset(vl) + seg * 1024);
         }
     }
     // same for a tile of 64 consecutive tokens starting at kh / vh
-    template <bool WITH_V = true>
+    template <bool WITH_V = true, bool WITH_K = true>
     __device__ __forceinline__ void issue_consecutive(const unsigned char* kh, const unsigned char* vh, unsigned char* kl,
                                                       unsigned char* vl) {
 #pragma unroll
         for (int j = 0; j < PER_WAVE; ++j) {
             const int seg = j * NW + wave;
             if (!EVEN && seg >= SEGS) break;
-            dma16(kh + j * STEP, k_lane_off[j % K_VARIANTS], lds_offset(kl) + seg * 1024);
+            if (WITH_K) dma16(kh + j * STEP, k_lane_off[j % K_VARIANTS], lds_offset(kl) + seg * 1024);
             if (WITH_V) dma16(vh + j * STEP, v_lane_off[j % V_VARIANTS], lds_offset(vl) + seg * 1024);
         }
     }
+    // load instructions per tensor and tile this wavefront issues (the first SEGS % NW wavefronts take the odd round)
+    __device__ __forceinline__ int loads_per_tensor() const { return EVEN ? PER_WAVE : (SEGS / NW + (wave < SEGS % NW ? 1 : 0)); }
     // Loads land in issue order.  A tile is in LDS once all but the loads issued after its own have
     // landed (the barrier that follows publishes it): LATER = how many whole tiles were issued after
     // it.  Every wavefront issues at least MIN_LOADS_PER_TILE loads per tile.
@@ -209,6 +212,21 @@ struct DirectTile {
     static __device__ __forceinline__ void wait_landed() {
         static_assert(LATER * MIN_LOADS_PER_TILE < 64, "vmcnt is a 6-bit counter");
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LATER * MIN_LOADS_PER_TILE) : "memory");
+    }
+
+    // The same wait with a wavefront-uniform run-time count: all but the newest n loads have landed.
+    static __device__ __forceinline__ void wait_all_but(int n) {
+        switch (n) {
+            case 1: asm volatile("s_waitcnt vmcnt(1)" ::: "memory"); break;
+            case 2: asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); break;
+            case 3: asm volatile("s_waitcnt vmcnt(3)" ::: "memory"); break;
+            case 4: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+            case 5: asm volatile("s_waitcnt vmcnt(5)" ::: "memory"); break;
+            case 6: asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); break;
+            case 7: asm volatile("s_waitcnt vmcnt(7)" ::: "memory"); break;
+            case 8: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+            default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+        }
     }
 
     // Per-tile LDS addresses of this lane's operands.  Both are made opaque once per tile, so that what

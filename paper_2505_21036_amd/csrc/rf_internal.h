@@ -101,6 +101,7 @@ struct AttnArgs {
     uint16_t* packed_v;
     const int32_t* head_bw;  // optional per-head index into plan[]; null or out of range: plan[0]
     int* queue;              // 8 work-queue counters and 8 sweep words (one each per XCD) at the start of the caller's workspace, reset by the launcher
+    int wide_rows;           // 1: wavefronts of 64 query rows (256-row blocks only)
     int join_sweep;          // 1: a starting item joins the tile walk of the workgroups already running on its XCD; 0: fixed start
     int n_plans;
     DevicePlan plan[kMaxBw];

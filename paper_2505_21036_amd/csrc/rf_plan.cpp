@@ -32,7 +32,7 @@ int resolve_geometry(const rf_layout* L, const rf_params* P, Geometry* g) {
     if (!(p->bw_spatial >= 0.f && p->bw_spatial <= 1.f)) return RF_ERR_PARAM;
     if (!(p->bw_temporal >= 0.f && p->bw_temporal <= 1.f)) return RF_ERR_PARAM;
     if (p->tex_stride < 1 || p->sample_interval < 0) return RF_ERR_PARAM;
-    if (p->flags & ~(RF_FLAG_TWO_HEAD | RF_FLAG_TEXT_FIRST | RF_FLAG_FORCE_DENSE | RF_FLAG_FIXED_ORDER)) return RF_ERR_PARAM;
+    if (p->flags & ~(RF_FLAG_TWO_HEAD | RF_FLAG_TEXT_FIRST | RF_FLAG_FORCE_DENSE | RF_FLAG_FIXED_ORDER | RF_FLAG_WIDE_ROWS)) return RF_ERR_PARAM;
     g->T = L->T; g->H = L->H; g->W = L->W; g->text_len = L->text_len;
     g->HW = static_cast<int>(HW); g->Nv = static_cast<int>(Nv); g->N = static_cast<int>(N);
     g->r_spatial = band_radius(p->bw_spatial, L->T);

@@ -430,6 +430,44 @@ def test_hunyuan720p_planted_layer_arm_picks_all_three_patterns():
     sampled_parity(w, O, classes, [(0, 3), (0, 4), (0, 5)], 16, tag="planted, arm-chosen, block 128, no copies")
 
 
+# ----------------------------------------------------------------------------- 64 query rows per wavefront
+@pytest.mark.parametrize("scale", [1.0, 12.0])
+@pytest.mark.parametrize("text_first", [False, True])
+def test_wide_rows_variant_every_class_every_row(scale, text_first):
+    """RF_FLAG_WIDE_ROWS (a wavefront owns 64 query rows, software-pipelined tile loop): every class,
+    gathered and packed, all rows of a ragged head_dim-128 shape (text rows, a ragged last block and
+    a ragged last key tile), also with the text rows first."""
+    w = inp.WORKLOADS["ragged128"]
+    print("case wide rows", scale, text_first, flush=True)
+    tl = w.text_len if text_first else 0
+    _, ol = lay(w)
+    rp = rf.rf_params(0.25, 0.25, 2, 0, rf.RF_FLAG_WIDE_ROWS | (rf.RF_FLAG_TEXT_FIRST if text_first else 0))
+    op = orc.Params(text_first=text_first)
+    Q, K, V = (torch.roll(t, tl, dims=2).contiguous() for t in inp.full_qkv(w, DEV, scale))
+    heads = {(b, h): [np.roll(f32(t), tl, axis=0) for t in inp.head_qkv(w, b, h, scale)]
+             for b in range(w.B) for h in range(w.nH)}
+    for cls, packed in ((rf.RF_SPATIAL, False), (rf.RF_TEMPORAL, False), (rf.RF_TEMPORAL, True),
+                        (rf.RF_TEXTURAL, False), (rf.RF_TEXTURAL, True), (rf.RF_DENSE, False)):
+        O = run_attention(w, Q, K, V, [cls] * (w.B * w.nH), 256, rp, packed)
+        for (b, h), (q, k, v) in heads.items():
+            check(O[b, h], orc.attention(q, k, v, cls, ol, op),
+                  "wide rows scale%g text-first%d cls%d packed%d head(%d,%d)" % (scale, text_first, cls, packed, b, h))
+
+
+def test_wide_rows_variant_at_the_headline_shape():
+    """The same variant on the planted heads of the headline shape, classes mixed in one launch, as
+    `bench.py --wide-rows` runs it: sampled rows against the oracle."""
+    w = inp.WORKLOADS["hunyuan720p_planted"]
+    print("case wide rows, hunyuan720p planted", flush=True)
+    Q, K, V = inp.full_qkv(w, DEV)
+    classes = [inp.planted_class(w, 0, h) for h in range(w.nH)]
+    rp = rf.rf_params(0.25, 0.25, 2, 0, rf.RF_FLAG_WIDE_ROWS)
+    O = run_attention(w, Q, K, V, classes, 256, rp, packed=True)
+    sampled_parity(w, O, classes, [(0, 0), (0, 1), (0, 2)], 16, tag="wide rows, planted classes, packed")
+    O = run_attention(w, Q, K, V, [rf.RF_DENSE] * w.nH, 256, rp)
+    sampled_parity(w, O, [rf.RF_DENSE] * w.nH, [(0, 7)], 8, tag="wide rows, dense")
+
+
 # ----------------------------------------------------------------------------- graphs and streams
 def test_step_replays_from_a_hip_graph():
     """ARM + attention captured once (after a warm-up call has built the block lists) and replayed

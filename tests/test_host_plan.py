@@ -246,7 +246,11 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     assert attn(lay=rf.rf_layout(0, 8, 8, 0)) == -3 and attn(lay=rf.rf_layout(4, 8, 8, -1)) == -3
     assert attn(lay=rf.rf_layout(4096, 4096, 4096, 0)) in (-2, -3)
     assert attn(par=rf.rf_params(1.5, 0.25, 2, 0)) == -4 and attn(par=rf.rf_params(0.25, -0.1, 2, 0)) == -4
-    assert attn(par=rf.rf_params(0.25, 0.25, 2, 0, 16)) == -4  # unknown flag
+    assert attn(par=rf.rf_params(0.25, 0.25, 2, 0, 32)) == -4  # unknown flag
+    # 64-row wavefronts exist for head_dim 128 with 256-row blocks only
+    wide = rf.rf_params(0.25, 0.25, 2, 0, rf.RF_FLAG_WIDE_ROWS)
+    assert attn(par=wide, D=64, block=256) == -4 and attn(par=wide, D=128, block=128) == -4
+    assert attn(par=wide, D=128, block=256, ws=None) == -6  # accepted up to the workspace check
     assert attn(par=rf.rf_params(0.25, 0.25, 0, 0)) == -4 and attn(par=rf.rf_params(float("nan"), 0.25, 2, 0)) == -4
     assert attn(block=32) == -5 and attn(block=512) == -5 and attn(block=0) == -5
     need = rf.rf_attention_workspace_bytes(1, 2, 64, L)
