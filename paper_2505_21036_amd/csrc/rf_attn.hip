@@ -84,9 +84,10 @@ constexpr float kRescaleSlack = 8.f;
 
 namespace rf {
 
-template <int D, int NW, int MODE>
+// QH: 32-query halves a wavefront owns (1, or 2: every K and V slab read from LDS then feeds two MFMAs).
+template <int D, int NW, int MODE, int QH = 1>
 __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, const QueryBlock& qk, unsigned char* smem) {
-    constexpr int BQ = 32 * NW;
+    constexpr int BQ = 32 * NW * QH;
     using ST = DirectTile<D, NW>;
     using SM = AttnSmem<D, NW>;
     constexpr int DEPTH = SM::DEPTH;
@@ -101,29 +102,43 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
     const unsigned char* Vh = qk.vbase;
     const uint16_t* Qh = a.Q + static_cast<size_t>(qk.bh) * N * D;
 
-    // this lane's query
-    const int qrow = qk.qb * BQ + wave * 32 + m;  // row of the walked order
-    const int qrow_c = min(qrow, N - 1);
-    const int qtok = (MODE == MODE_LISTED && qk.row_token) ? qk.row_token[qrow_c]
-                                                           : qrow_c + (qrow_c < Nv ? pl.video_shift : pl.text_shift);
-    bf16x8 qf[D / 16];
-    load_q_frags<D>(Qh, qtok, hf, qf);
-    int q_attr = 0, q_rad = 0x3fffffff;  // text queries keep everything
-    if (MODE == MODE_LISTED) {
-        // Spatial / Temporal compare the query's frame / position with the key's; the Textural
-        // table is 0 on kept keys and 1 on dropped ones, compared against 0 with radius 0
-        if (qk.cls != RF_TEXTURAL) q_attr = side_src[qrow_c];
-        if (qrow_c < Nv) q_rad = pl.radius[qk.list];
-    }
-    const uint32_t q_lo = static_cast<uint32_t>(q_rad - q_attr), q_span = 2u * static_cast<uint32_t>(q_rad);
-
-    f32x16 oacc[D / 32];
+    // this lane's queries, one per half
+    int qrow[QH], qtok[QH];
+    bf16x8 qf[QH][D / 16];
+    uint32_t q_lo[QH], q_span[QH];
 #pragma unroll
-    for (int db = 0; db < D / 32; ++db) oacc[db] = f32x16{0};
+    for (int h = 0; h < QH; ++h) {
+        qrow[h] = qk.qb * BQ + wave * (32 * QH) + 32 * h + m;  // row of the walked order
+        const int qrow_c = min(qrow[h], N - 1);
+        qtok[h] = (MODE == MODE_LISTED && qk.row_token) ? qk.row_token[qrow_c]
+                                                        : qrow_c + (qrow_c < Nv ? pl.video_shift : pl.text_shift);
+        load_q_frags<D>(Qh, qtok[h], hf, qf[h]);
+        int q_attr = 0, q_rad = 0x3fffffff;  // text queries keep everything
+        if (MODE == MODE_LISTED) {
+            // Spatial / Temporal compare the query's frame / position with the key's; the Textural
+            // table is 0 on kept keys and 1 on dropped ones, compared against 0 with radius 0
+            if (qk.cls != RF_TEXTURAL) q_attr = side_src[qrow_c];
+            if (qrow_c < Nv) q_rad = pl.radius[qk.list];
+        }
+        q_lo[h] = static_cast<uint32_t>(q_rad - q_attr);
+        q_span[h] = 2u * static_cast<uint32_t>(q_rad);
+    }
+
+    f32x16 oacc[QH][D / 32];
+#pragma unroll
+    for (int h = 0; h < QH; ++h)
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) oacc[h][db] = f32x16{0};
     // m_ref: reference subtracted inside exp2 (raw score units), finite from the start; has_ref: it has
     // been taken from real scores of this row; l_run: this lane's share of the softmax denominator
-    float m_ref = 0.f, l_run = 0.f;
-    bool has_ref = false;
+    float m_ref[QH], l_run[QH];
+    bool has_ref[QH];
+#pragma unroll
+    for (int h = 0; h < QH; ++h) {
+        m_ref[h] = 0.f;
+        l_run[h] = 0.f;
+        has_ref[h] = false;
+    }
     const float c = a.scale_log2;
 
     ST st;
@@ -186,53 +201,71 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
         }
     };
 
-    // S^T of tile t (64 keys x this lane's query), predicate applied where the tile is partial
-    auto scores = [&](int t, int entry, f32x16 (&s)[2]) {
-        st.template scores<kAheadK>(st.k_address(k_lds(t)), qf, s);
+    // S^T of tile t (64 keys x this lane's query of each half), predicate applied where the tile is partial
+    auto scores = [&](int t, int entry, f32x16 (&s)[QH][2]) {
+        if (QH == 1) {
+            st.template scores<kAheadK>(st.k_address(k_lds(t)), qf[0], s[0]);
+        } else {
+            // as DirectTile::scores, every K slab feeding one MFMA per half
+            constexpr int NQK = 2 * (D / 16);
+            const uint32_t ka = st.k_address(k_lds(t));
+            bf16x8 frag[NQK];
+#pragma unroll
+            for (int i = 0; i < kAheadK; ++i) frag[i] = st.k_frag(ka, i & 1, i >> 1);
+#pragma unroll
+            for (int h = 0; h < QH; ++h) {
+                s[h][0] = f32x16{0};
+                s[h][1] = f32x16{0};
+            }
+#pragma unroll
+            for (int j = 0; j < NQK; ++j) {
+                if (j + kAheadK < NQK) frag[j + kAheadK] = st.k_frag(ka, (j + kAheadK) & 1, (j + kAheadK) >> 1);
+#pragma unroll
+                for (int h = 0; h < QH; ++h) {
+                    s[h][j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[j], qf[h][j >> 1], s[h][j & 1], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
         if (entry & RF_PLAN_PARTIAL) {
             const int k0 = (entry & kTileIndexMask) * kTileK;
             const int* al = side + (t % SM::SIDE_SLOTS) * kTileK;
-            if (MODE == MODE_LISTED && !(entry & kTileBoundary)) {
-                // all 64 keys are video tokens: only the pattern's band decides
 #pragma unroll
-                for (int kb2 = 0; kb2 < 2; ++kb2)
+            for (int h = 0; h < QH; ++h) {
+                if (MODE == MODE_LISTED && !(entry & kTileBoundary)) {
+                    // all 64 keys are video tokens: only the pattern's band decides
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const uint32_t d = static_cast<uint32_t>(al[32 * kb2 + key_of_reg(r, hf)]) + q_lo;
-                        s[kb2][r] = d <= q_span ? s[kb2][r] : -INFINITY;
-                    }
-            } else {
+                    for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
-                for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int koff = 32 * kb2 + key_of_reg(r, hf);
-                        const int kidx = k0 + koff;
-                        bool ok = kidx < keyN;
-                        if (MODE == MODE_LISTED) {
-                            const uint32_t d = static_cast<uint32_t>(al[koff]) + q_lo;
-                            ok = ok & ((d <= q_span) | (kidx >= Nv));
+                        for (int r = 0; r < 16; ++r) {
+                            const uint32_t d = static_cast<uint32_t>(al[32 * kb2 + key_of_reg(r, hf)]) + q_lo[h];
+                            s[h][kb2][r] = d <= q_span[h] ? s[h][kb2][r] : -INFINITY;
                         }
-                        s[kb2][r] = ok ? s[kb2][r] : -INFINITY;
-                    }
+                } else {
+#pragma unroll
+                    for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int koff = 32 * kb2 + key_of_reg(r, hf);
+                            const int kidx = k0 + koff;
+                            bool ok = kidx < keyN;
+                            if (MODE == MODE_LISTED) {
+                                const uint32_t d = static_cast<uint32_t>(al[koff]) + q_lo[h];
+                                ok = ok & ((d <= q_span[h]) | (kidx >= Nv));
+                            }
+                            s[h][kb2][r] = ok ? s[h][kb2][r] : -INFINITY;
+                        }
+                }
             }
         }
     };
-    // p = exp2((s - m_ref) * c) in place
-    auto exponentiate = [&](f32x16 (&s)[2]) {
-        const float mc = m_ref * c;
-#pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[kb2][r] = fast_exp2(fmaf(s[kb2][r], c, -mc));
-    };
 
     // O^T += V^T P^T for tile t, P (bf16) in pf
-    bf16x8 pf[4];
+    bf16x8 pf[QH][4];
     auto accumulate = [&](int t) {
         const uint32_t va = st.v_address(v_lds(t));
-        // consecutive MFMAs go to different accumulators (channel blocks): no back-to-back dependence;
-        // operand reads kAheadV MFMAs ahead, order fenced as for the scores
+        // consecutive MFMAs go to different accumulators (channel blocks, halves): no back-to-back
+        // dependence; operand reads kAheadV slabs ahead, order fenced as for the scores
         constexpr int NPV = 4 * (D / 32), NDB = D / 32;
         bf16x8 frag[NPV];
 #pragma unroll
@@ -240,8 +273,11 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
 #pragma unroll
         for (int j = 0; j < NPV; ++j) {
             if (j + kAheadV < NPV) frag[j + kAheadV] = ST::v_frag(va, (j + kAheadV) % NDB, (j + kAheadV) / NDB);
-            oacc[j % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[j], pf[j / NDB], oacc[j % NDB], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int h = 0; h < QH; ++h) {
+                oacc[h][j % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[j], pf[h][j / NDB], oacc[h][j % NDB], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     };
     // Software pipeline.  While tile t is consumed, the loads of tiles t+1 .. t+AHEAD are in flight
@@ -265,7 +301,9 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
     // The compiler cannot see the tile loads above, so its own wait for the Q loads, if left inside
     // the loop, would count them out too and wait for the tiles in flight; make it wait here.
 #pragma unroll
-    for (int cc = 0; cc < D / 16; ++cc) asm volatile("" ::"v"(__builtin_bit_cast(u32x4, qf[cc])));
+    for (int h = 0; h < QH; ++h)
+#pragma unroll
+        for (int cc = 0; cc < D / 16; ++cc) asm volatile("" ::"v"(__builtin_bit_cast(u32x4, qf[h][cc])));
 
     for (int t = 0; t < ntiles; ++t) {
         // the buffer of tile t+AHEAD held tile t+AHEAD-DEPTH, which every wavefront left before the last barrier
@@ -280,7 +318,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
         // Online softmax (Eq. 1) in base 2 with 1/sqrt(D) folded into c.  The reference subtracted in
         // the exponent is moved, and the accumulators rescaled, only when a row outgrows it by more
         // than 2^kRescaleSlack (or has none yet): the softmax does not depend on the reference.
-        f32x16 s[2];
+        f32x16 s[QH][2];
         scores(t, e_cur, s);
         // With eight wavefronts at head_dim 128 the softmax section (VALU only) runs at raised
         // priority and the two MFMA sections at the default: the wavefront that shares the SIMD is
@@ -288,43 +326,51 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
         // +1 % there; neutral at head_dim 96 and 1-4 % slower with four wavefronts, so not there).
         constexpr bool kSoftmaxPriority = D == 128 && NW == 8;
         if (kSoftmaxPriority) __builtin_amdgcn_s_setprio(1);
-        float mt = s[0][0];
 #pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2)
+        for (int h = 0; h < QH; ++h) {
+            float mt = s[h][0][0];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mt = fmaxf(mt, s[kb2][r]);
-        // the two halves of the wavefront hold different keys of the same 32 queries: their maxima
-        // are exchanged only when some lane asks for the reference to move
-        const bool grow = has_ref ? (mt - m_ref) * c > kRescaleSlack : mt > -INFINITY;
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-            mt = fmaxf(mt, other_half(mt));
-            if (mt > -INFINITY) {
-                const float m_new = has_ref ? fmaxf(m_ref, mt) : mt;
-                const float alpha = has_ref ? fast_exp2((m_ref - m_new) * c) : 0.f;  // nothing accumulated before
-                l_run *= alpha;
+            for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
-                for (int db = 0; db < D / 32; ++db)
+                for (int r = 0; r < 16; ++r) mt = fmaxf(mt, s[h][kb2][r]);
+            // the two halves of the wavefront hold different keys of the same 32 queries: their maxima
+            // are exchanged only when some lane asks for the reference to move
+            const bool grow = has_ref[h] ? (mt - m_ref[h]) * c > kRescaleSlack : mt > -INFINITY;
+            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                mt = fmaxf(mt, other_half(mt));
+                if (mt > -INFINITY) {
+                    const float m_new = has_ref[h] ? fmaxf(m_ref[h], mt) : mt;
+                    const float alpha = has_ref[h] ? fast_exp2((m_ref[h] - m_new) * c) : 0.f;  // nothing accumulated before
+                    l_run[h] *= alpha;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-                m_ref = m_new;
-                has_ref = true;
+                    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) oacc[h][db][r] *= alpha;
+                    m_ref[h] = m_new;
+                    has_ref[h] = true;
+                }
             }
+            // p = exp2((s - m_ref) * c) in place
+            const float mc = m_ref[h] * c;
+#pragma unroll
+            for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[h][kb2][r] = fast_exp2(fmaf(s[h][kb2][r], c, -mc));
+            // P is rounded to bf16 for the second MFMA; the denominator sums those same rounded values
+            // (two per v_dot2c_f32_bf16), so numerator and denominator of Eq. 2 see identical weights
+#pragma unroll
+            for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+                for (int u2 = 0; u2 < 2; ++u2) {
+                    u32x4 w;
+                    w.x = pack_bf16(s[h][kb2][8 * u2 + 0], s[h][kb2][8 * u2 + 1]);
+                    w.y = pack_bf16(s[h][kb2][8 * u2 + 2], s[h][kb2][8 * u2 + 3]);
+                    w.z = pack_bf16(s[h][kb2][8 * u2 + 4], s[h][kb2][8 * u2 + 5]);
+                    w.w = pack_bf16(s[h][kb2][8 * u2 + 6], s[h][kb2][8 * u2 + 7]);
+                    l_run[h] = add_bf16_pair(add_bf16_pair(add_bf16_pair(add_bf16_pair(l_run[h], w.x), w.y), w.z), w.w);
+                    pf[h][2 * kb2 + u2] = as_bf16x8(w);
+                }
         }
-        exponentiate(s);
-        // P is rounded to bf16 for the second MFMA; the denominator sums those same rounded values
-        // (two per v_dot2c_f32_bf16), so numerator and denominator of Eq. 2 see identical weights
-#pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-            for (int u2 = 0; u2 < 2; ++u2) {
-                u32x4 w;
-                w.x = pack_bf16(s[kb2][8 * u2 + 0], s[kb2][8 * u2 + 1]);
-                w.y = pack_bf16(s[kb2][8 * u2 + 2], s[kb2][8 * u2 + 3]);
-                w.z = pack_bf16(s[kb2][8 * u2 + 4], s[kb2][8 * u2 + 5]);
-                w.w = pack_bf16(s[kb2][8 * u2 + 6], s[kb2][8 * u2 + 7]);
-                l_run = add_bf16_pair(add_bf16_pair(add_bf16_pair(add_bf16_pair(l_run, w.x), w.y), w.z), w.w);
-                pf[2 * kb2 + u2] = as_bf16x8(w);
-            }
         if (kSoftmaxPriority) __builtin_amdgcn_s_setprio(0);
         accumulate(t);
 
@@ -338,29 +384,42 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
     }
     // Eq. 2: divide by the softmax denominator and store.  Lane (hf, m) owns query m and, per
     // 32-channel block, channels 8*(r/4) + 4*hf + r%4.
-    const float l_tot = l_run + other_half(l_run);
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    if (qrow < N) {
-        uint16_t* orow = a.O + static_cast<size_t>(qk.bh) * N * D + static_cast<size_t>(qtok) * D;
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db)
+    for (int h = 0; h < QH; ++h) {
+        const float l_tot = l_run[h] + other_half(l_run[h]);
+        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+        if (qrow[h] < N) {
+            uint16_t* orow = a.O + static_cast<size_t>(qk.bh) * N * D + static_cast<size_t>(qtok[h]) * D;
 #pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                u32x2 w;
-                w.x = pack_bf16(oacc[db][4 * rq + 0] * inv, oacc[db][4 * rq + 1] * inv);
-                w.y = pack_bf16(oacc[db][4 * rq + 2] * inv, oacc[db][4 * rq + 3] * inv);
-                *reinterpret_cast<u32x2*>(orow + 32 * db + 8 * rq + 4 * hf) = w;
-            }
+            for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    u32x2 w;
+                    w.x = pack_bf16(oacc[h][db][4 * rq + 0] * inv, oacc[h][db][4 * rq + 1] * inv);
+                    w.y = pack_bf16(oacc[h][db][4 * rq + 2] * inv, oacc[h][db][4 * rq + 3] * inv);
+                    *reinterpret_cast<u32x2*>(orow + 32 * db + 8 * rq + 4 * hf) = w;
+                }
+        }
     }
 }
 
-// Wavefronts per SIMD the register allocation is held to: three for head_dim 64 with 128-row
-// blocks (measured best; its accumulators are half the size), two otherwise; one for wavefronts of
-// 64 query rows (WIDE), which need the whole register file.
-constexpr int attn_waves_per_simd(int D, int NW, bool WIDE) { return WIDE ? 1 : (D == 64 && NW == 4) ? 3 : 2; }  // NW = 8: one workgroup per CU
+// Which tile loop a kernel instance runs.
+enum : int {
+    LOOP_32 = 0,           // wavefronts of 32 query rows (attend)
+    LOOP_64_PIPELINED = 1, // wavefronts of 64 rows, one per SIMD, software-pipelined (attend_wide)
+    LOOP_64 = 2            // wavefronts of 64 rows on the plain loop (attend with two halves): head_dim 64 only, where two fit a SIMD
+};
+constexpr int rows_per_wave(int LOOP) { return LOOP == LOOP_32 ? 32 : 64; }
 
-template <int D, int NW, bool WIDE>
-using SmemOf = std::conditional_t<WIDE, WideSmem<D, NW>, AttnSmem<D, NW>>;
+// Wavefronts per SIMD the register allocation is held to: three for head_dim 64 with 128-row
+// blocks of 32-row wavefronts (measured best; its accumulators are half the size), two otherwise; one
+// for the pipelined 64-row loop, which needs the whole register file.
+constexpr int attn_waves_per_simd(int D, int NW, int LOOP) {
+    return LOOP == LOOP_64_PIPELINED ? 1 : (LOOP == LOOP_32 && D == 64 && NW == 4) ? 3 : 2;
+}
+
+template <int D, int NW, int LOOP>
+using SmemOf = std::conditional_t<LOOP == LOOP_64_PIPELINED, WideSmem<D, NW>, AttnSmem<D, NW>>;
 
 // Items of one launch.  Queue x holds first its share of the long items (the nTB text-holding blocks
 // of every head: global index i = head * nTB + k goes to queue i mod 8), then, head after head, the
@@ -407,7 +466,7 @@ __device__ __forceinline__ int item_head(int item, int xcd, const Queues& qs) {
     return item < longs ? (item * 8 + xcd) / qs.nTB : (item - longs) / qs.share(xcd);
 }
 
-template <int D, int NW, bool WIDE>
+template <int D, int NW, int LOOP>
 __device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xcd, int seen, const Queues& qs, unsigned char* smem);
 
 // Eight queue counters, then the sweep words (-1: nothing published yet).
@@ -415,11 +474,11 @@ __global__ void reset_queue_kernel(int* ctr) {
     if (threadIdx.x < kQueueWords) ctr[threadIdx.x] = threadIdx.x < 8 ? 0 : -1;
 }
 
-// NW wavefronts of 32 query rows each, or (WIDE) of 64.
-template <int D, int NW, bool WIDE>
-__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(attn_waves_per_simd(D, NW, WIDE), attn_waves_per_simd(D, NW, WIDE)))) attn_kernel(AttnArgs a) {
+// NW wavefronts of rows_per_wave(LOOP) query rows each.
+template <int D, int NW, int LOOP>
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(attn_waves_per_simd(D, NW, LOOP), attn_waves_per_simd(D, NW, LOOP)))) attn_kernel(AttnArgs a) {
     extern __shared__ __attribute__((aligned(256))) unsigned char smem[];  // the kernel's only LDS: starts at address 0
-    int* item_box = reinterpret_cast<int*>(smem + SmemOf<D, NW, WIDE>::ITEM_OFF);
+    int* item_box = reinterpret_cast<int*>(smem + SmemOf<D, NW, LOOP>::ITEM_OFF);
     // A resident set of workgroups (as many as fit on the chip) works through the (head, query
     // block) items.  Workgroup ids go to the 8 XCDs round-robin; XCD x's queue is one eighth of every
     // head's block order, head after head (neighbours in that order walk nearly the same key tiles,
@@ -450,18 +509,18 @@ __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(at
         const int seen = __builtin_amdgcn_readfirstlane(item_box[2]);
         __syncthreads();
         if (item < 0) break;
-        process_item<D, NW, WIDE>(a, item, xcd, seen, qs, smem);
+        process_item<D, NW, LOOP>(a, item, xcd, seen, qs, smem);
     }
 }
 
 // One (head, query block) item: item-th of queue xcd.  seen: the sweep word of this workgroup's XCD
 // (it serves its own L2, whichever queue the item came from), or -1.
-template <int D, int NW, bool WIDE>
+template <int D, int NW, int LOOP>
 __device__ __forceinline__ void process_item(const AttnArgs& a, int item, int xcd, int seen, const Queues& qs, unsigned char* smem) {
     auto run = [&](auto mode, const DevicePlan& plan, const QueryBlock& block) {
         constexpr int MODE = decltype(mode)::value;
-        if constexpr (WIDE) attend_wide<D, NW, MODE>(a, plan, block, smem);
-        else attend<D, NW, MODE>(a, plan, block, smem);
+        if constexpr (LOOP == LOOP_64_PIPELINED) attend_wide<D, NW, MODE>(a, plan, block, smem);
+        else attend<D, NW, MODE, rows_per_wave(LOOP) / 32>(a, plan, block, smem);
     };
     // position in the block order, and the head
     int ordinal, bh;
@@ -587,10 +646,10 @@ int launch_pack_textural(const AttnArgs& a, int D, void* stream) {
     return static_cast<int>(hipGetLastError());
 }
 
-template <int D, int NW, bool WIDE = false>
+template <int D, int NW, int LOOP = LOOP_32>
 static int launch_one(const AttnArgs& a, hipStream_t st) {
     constexpr int NT = 64 * NW;
-    constexpr int smem = SmemOf<D, NW, WIDE>::BYTES;
+    constexpr int smem = SmemOf<D, NW, LOOP>::BYTES;
     // workgroups each device holds at once, found on first use there (which also raises the kernel's dynamic-LDS limit)
     constexpr int kMaxDevices = 64;
     static std::mutex mu;
@@ -603,12 +662,12 @@ static int launch_one(const AttnArgs& a, hipStream_t st) {
     {
         std::lock_guard<std::mutex> lock(mu);
         if (resident_on[dev] == 0) {
-            const void* fn = reinterpret_cast<const void*>(&attn_kernel<D, NW, WIDE>);
+            const void* fn = reinterpret_cast<const void*>(&attn_kernel<D, NW, LOOP>);
             e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
             if (e != hipSuccess) return static_cast<int>(e);
             int cus = 0, per_cu = 0;
             if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return static_cast<int>(e);
-            if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_kernel<D, NW, WIDE>, NT, smem)) != hipSuccess)
+            if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_kernel<D, NW, LOOP>, NT, smem)) != hipSuccess)
                 return static_cast<int>(e);
             if (cus < 1 || per_cu < 1) return static_cast<int>(hipErrorInvalidValue);
             resident_on[dev] = cus * per_cu;
@@ -620,16 +679,15 @@ static int launch_one(const AttnArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(reset_queue_kernel, dim3(1), dim3(64), 0, st, a.queue);
     e = hipGetLastError();
     if (e != hipSuccess) return static_cast<int>(e);
-    hipLaunchKernelGGL((attn_kernel<D, NW, WIDE>), dim3(grid), dim3(NT), smem, st, a);
+    hipLaunchKernelGGL((attn_kernel<D, NW, LOOP>), dim3(grid), dim3(NT), smem, st, a);
     return static_cast<int>(hipGetLastError());
 }
 
 int launch_attention(const AttnArgs& a, int D, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int nw = a.plan[0].block / 32;
-    if (a.wide_rows) {  // 64 query rows per wavefront: 256-row blocks as four wavefronts
-        if (nw != 8) return static_cast<int>(hipErrorInvalidValue);
-        if (D == 128) return launch_one<128, 4, true>(a, st);
+    if (a.wide_rows) {  // the pipelined loop for 64-row wavefronts: 256-row blocks as four wavefronts, head_dim 128
+        if (D == 128 && nw == 8) return launch_one<128, 4, LOOP_64_PIPELINED>(a, st);
         return static_cast<int>(hipErrorInvalidValue);
     }
     if (D == 64 && nw == 2) return launch_one<64, 2>(a, st);
@@ -638,7 +696,9 @@ int launch_attention(const AttnArgs& a, int D, void* stream) {
     if (D == 96 && nw == 4) return launch_one<96, 4>(a, st);
     if (D == 128 && nw == 2) return launch_one<128, 2>(a, st);
     if (D == 128 && nw == 4) return launch_one<128, 4>(a, st);
-    if (D == 64 && nw == 8) return launch_one<64, 8>(a, st);
+    // 256-row blocks at head_dim 64: four wavefronts of 64 rows (two still fit a SIMD; measured 8-15 %
+    // faster than eight of 32: half the LDS operand reads and half the per-tile bookkeeping per MFMA)
+    if (D == 64 && nw == 8) return launch_one<64, 4, LOOP_64>(a, st);
     if (D == 96 && nw == 8) return launch_one<96, 8>(a, st);
     if (D == 128 && nw == 8) return launch_one<128, 8>(a, st);
     return static_cast<int>(hipErrorInvalidValue);

@@ -54,7 +54,7 @@ def test_tile_loops_keep_operand_reads_ahead_of_the_mfmas():
     waits for all-but-3 / all-but-4 outstanding LDS operations.  (A schedule that reads, waits for
     everything and then issues one MFMA costs ~9 % and has appeared from unrelated edits.)"""
     asm = device_assembly("rf_attn.hip")
-    loops = _tile_loops(asm, "_ZN2rf11attn_kernelILi128ELi8ELb0EEEvNS_8AttnArgsE")
+    loops = _tile_loops(asm, "_ZN2rf11attn_kernelILi128ELi8ELi0EEEvNS_8AttnArgsE")
     assert len(loops) >= 3  # every-tile walk (dense / packed), compacted walk, listed walk
     for body in loops:
         waits = [x for x in body if x.startswith("s_waitcnt") and "lgkmcnt" in x]
