@@ -91,6 +91,10 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
     using ST = DirectTile<D, NW>;
     using SM = AttnSmem<D, NW>;
     constexpr int DEPTH = SM::DEPTH;
+    // how many slabs ahead of their MFMAs the LDS operand reads run: with two halves every slab feeds two
+    // MFMAs and the registers are all in use, and two measured best (dense CogVideoX-shaped layer 4.25 ->
+    // 3.99 ms against the depths of the one-half loop)
+    constexpr int AK = QH == 2 ? 2 : kAheadK, AV = QH == 2 ? 2 : kAheadV;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, m = lane & 31;
     const int N = pl.N, Nv = pl.Nv, keyN = qk.keyN, ntiles = qk.ntiles;
     // per-key side data staged through LDS two tiles ahead: the token index of each key of the
@@ -204,14 +208,14 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
     // S^T of tile t (64 keys x this lane's query of each half), predicate applied where the tile is partial
     auto scores = [&](int t, int entry, f32x16 (&s)[QH][2]) {
         if (QH == 1) {
-            st.template scores<kAheadK>(st.k_address(k_lds(t)), qf[0], s[0]);
+            st.template scores<AK>(st.k_address(k_lds(t)), qf[0], s[0]);
         } else {
             // as DirectTile::scores, every K slab feeding one MFMA per half
             constexpr int NQK = 2 * (D / 16);
             const uint32_t ka = st.k_address(k_lds(t));
             bf16x8 frag[NQK];
 #pragma unroll
-            for (int i = 0; i < kAheadK; ++i) frag[i] = st.k_frag(ka, i & 1, i >> 1);
+            for (int i = 0; i < AK; ++i) frag[i] = st.k_frag(ka, i & 1, i >> 1);
 #pragma unroll
             for (int h = 0; h < QH; ++h) {
                 s[h][0] = f32x16{0};
@@ -219,7 +223,7 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
             }
 #pragma unroll
             for (int j = 0; j < NQK; ++j) {
-                if (j + kAheadK < NQK) frag[j + kAheadK] = st.k_frag(ka, (j + kAheadK) & 1, (j + kAheadK) >> 1);
+                if (j + AK < NQK) frag[j + AK] = st.k_frag(ka, (j + AK) & 1, (j + AK) >> 1);
 #pragma unroll
                 for (int h = 0; h < QH; ++h) {
                     s[h][j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[j], qf[h][j >> 1], s[h][j & 1], 0, 0, 0);
@@ -269,10 +273,10 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
         constexpr int NPV = 4 * (D / 32), NDB = D / 32;
         bf16x8 frag[NPV];
 #pragma unroll
-        for (int i = 0; i < kAheadV; ++i) frag[i] = ST::v_frag(va, i % NDB, i / NDB);
+        for (int i = 0; i < AV; ++i) frag[i] = ST::v_frag(va, i % NDB, i / NDB);
 #pragma unroll
         for (int j = 0; j < NPV; ++j) {
-            if (j + kAheadV < NPV) frag[j + kAheadV] = ST::v_frag(va, (j + kAheadV) % NDB, (j + kAheadV) / NDB);
+            if (j + AV < NPV) frag[j + AV] = ST::v_frag(va, (j + AV) % NDB, (j + AV) / NDB);
 #pragma unroll
             for (int h = 0; h < QH; ++h) {
                 oacc[h][j % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[j], pf[h][j / NDB], oacc[h][j % NDB], 0, 0, 0);
