@@ -337,6 +337,7 @@ __device__ __forceinline__ void attend_wide(const AttnArgs& a, const DevicePlan&
     ST st;
     st.init(tid);
     const int loads_per_tensor = st.loads_per_tensor();
+    static_assert(2 * ST::PER_WAVE <= 8, "wait_all_but() knows counts up to 8");
     auto k_lds = [&](int t) { return smem + SM::K_OFF + (t % SM::K_RING) * ST::K_BYTES; };
     auto v_lds = [&](int t) { return smem + SM::V_OFF + (t % SM::V_RING) * ST::V_BYTES; };
     auto side_slot = [&](int t) { return side + (t % SM::SIDE_SLOTS) * kTileK; };
