@@ -332,9 +332,10 @@ def test_plus_attention_with_a_workspace_and_two_bandwidths_per_pattern(text_fir
     hc = torch.as_tensor(classes, dtype=torch.int32).reshape(w.B, w.nH).to(DEV)
     hbw = torch.as_tensor(chosen, dtype=torch.int32).reshape(w.B, w.nH).to(DEV)
     ws = torch.empty(rf.rf_attention_workspace_bytes(w.B, w.nH, w.D, rl, rp), dtype=torch.uint8, device=DEV)
-    for block in (64, 128, 256):
+    rp_wide = rf.rf_params(0.25, 0.25, 2, 0, rp.flags | rf.RF_FLAG_WIDE_ROWS)  # the 64-row loop with a list per head
+    for block, params in ((64, rp), (128, rp), (256, rp), (256, rp_wide)):
         for workspace in (ws, None):
-            O = rf.rf_sparse_attention_plus(Q, K, V, hc, hbw, bws, rl, rp, block, workspace=workspace)
+            O = rf.rf_sparse_attention_plus(Q, K, V, hc, hbw, bws, rl, params, block, workspace=workspace)
             torch.cuda.synchronize()
             for b in range(w.B):
                 for h in range(w.nH):
