@@ -55,7 +55,7 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="hunyuan720p")
-    ap.add_argument("--block", type=int, default=0, help="query rows per block (64|128|256); 0 = the workload's")
+    ap.add_argument("--block", type=int, default=0, help="query rows per block (64|128|256, 384 at head_dim 96); 0 = the workload's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wide-rows", action="store_true",
                     help="run the attention with RF_FLAG_WIDE_ROWS (64 query rows per wavefront; head_dim 128, block 256)")
@@ -217,7 +217,7 @@ def main():
 
         time_config("cogvideox", (128, 256), forced=inp.round_robin_classes)
         time_config("cogvideox", (128, 256), arm_mode=rf.RF_SAMPLE_EQUAL_INTERVAL)
-        time_config("osp720p", (128, 256), forced=inp.thirds_classes)
+        time_config("osp720p", (128, 256, 384), forced=inp.thirds_classes)
         time_config("planted", (64, 128), arm_mode=rf.RF_SAMPLE_FIRST_FRAME)
         print(json.dumps({"configs": rows}))
         return

@@ -55,7 +55,7 @@ WORKLOADS = {
     # CogVideoX-5B-shaped layer, 226 text tokens
     "cogvideox": Workload("cogvideox", 1, 48, 64, 13, 30, 45, 226, 256, 1002),
     # Open-Sora-Plan-1.2 720p-shaped layer
-    "osp720p": Workload("osp720p", 1, 24, 96, 24, 45, 80, 0, 256, 1003),
+    "osp720p": Workload("osp720p", 1, 24, 96, 24, 45, 80, 0, 384, 1003),
     # HunyuanVideo 720p-shaped layer, 256 text tokens (headline)
     "hunyuan720p": Workload("hunyuan720p", 1, 24, 128, 33, 45, 80, 256, 256, 1004),
     # planted-structure ARM validation

@@ -38,7 +38,7 @@ static int check_plans() {
             if (big && &P != &params[0] && &P != &params[3]) continue;  // the paper-sized layouts: two settings are enough
             rf::Geometry g;
             if (rf::resolve_geometry(&L, &P, &g) != RF_OK) return fail("resolve_geometry refused a valid layout");
-            for (int block : {64, 128, 256}) {
+            for (int block : {64, 128, 256, 384}) {
                 rf::HostPlan hp;
                 rf::build_plan(g, block, &hp);
                 for (int cls = RF_SPATIAL; cls <= RF_LIST_TEMPORAL_POSITION_MAJOR; ++cls) {

@@ -64,10 +64,12 @@ SMALL = ["tiny", "ragged64", "ragged96", "ragged128"]
 
 
 @pytest.mark.parametrize("name", SMALL)
-@pytest.mark.parametrize("block", [64, 128, 256])
+@pytest.mark.parametrize("block", [64, 128, 256, 384])
 @pytest.mark.parametrize("scale", [1.0, 12.0])
 def test_small_shapes_every_class_every_row(name, block, scale):
     w = inp.WORKLOADS[name]
+    if block == 384 and w.D != 96:
+        pytest.skip("384-row blocks exist at head_dim 96 only")
     print("case", name, block, scale, flush=True)
     rp, op = par()
     _, ol = lay(w)
@@ -143,11 +145,13 @@ def test_out_of_range_class_runs_dense_and_constant_values_give_ones():
 
 # ----------------------------------------------------------------------------- text tokens first, forced dense
 @pytest.mark.parametrize("name", ["ragged64", "ragged96", "ragged128"])
-@pytest.mark.parametrize("block", [64, 128, 256])
+@pytest.mark.parametrize("block", [64, 128, 256, 384])
 def test_text_first_every_class_every_row(name, block):
     """The same heads with their text rows moved to the front and RF_FLAG_TEXT_FIRST set, against
     the oracle's text-first reading; attention for every class, packed or not, and the ARM."""
     w = inp.WORKLOADS[name]
+    if block == 384 and w.D != 96:
+        pytest.skip("384-row blocks exist at head_dim 96 only")
     print("case text-first", name, block, flush=True)
     tl, scale = w.text_len, 6.0
     rl, ol = lay(w)
@@ -384,6 +388,8 @@ def test_osp720p_layer_sparse_and_dense():
     sampled_parity(w, O, classes, [(0, 0), (0, 9), (0, 23)], 20, tag="thirds")
     O = run_attention(w, Q, K, V, classes, 128, packed=True)  # the block size the configuration names
     sampled_parity(w, O, classes, [(0, 1), (0, 10), (0, 22)], 20, tag="thirds, packed, block 128")
+    O = run_attention(w, Q, K, V, classes, 256, packed=True)
+    sampled_parity(w, O, classes, [(0, 2), (0, 12), (0, 19)], 12, tag="thirds, packed, block 256")
     dense = [rf.RF_DENSE] * w.nH
     O = run_attention(w, Q, K, V, dense, w.block)
     sampled_parity(w, O, dense, [(0, 11)], 12, tag="dense")
@@ -588,7 +594,7 @@ def test_random_small_configurations():
         B, nH = int(rng.integers(1, 3)), int(rng.integers(1, 6))
         bs, bt = float(rng.choice([0.0, 0.07, 0.25, 0.5, 1.0])), float(rng.choice([0.0, 0.03, 0.25, 0.6, 1.0]))
         tau = int(rng.integers(1, 6))
-        block = int(rng.choice([64, 128, 256]))
+        block = int(rng.choice([64, 128, 256] + ([384, 384] if D == 96 else [])))
         packed, text_first = bool(rng.integers(0, 2)), bool(rng.integers(0, 2)) and tl > 0
         scale = float(rng.choice([1.0, 4.0, 10.0]))
         w = inp.Workload("rand%d" % case, B, nH, D, T, H, W, tl, block, 5000 + case)

@@ -46,7 +46,7 @@ def brute_blocks(M, block):
 
 @pytest.mark.parametrize("lay", LAYOUTS)
 @pytest.mark.parametrize("par", PARAMS)
-@pytest.mark.parametrize("block", [64, 128, 256])
+@pytest.mark.parametrize("block", [64, 128, 256, 384])
 def test_block_lists_match_brute_force(lay, par, block):
     L, P = orc.Layout(*lay), orc.Params(par[0], par[1], par[2])
     rl, rp = rf.rf_layout(*lay), rf.rf_params(par[0], par[1], par[2], 0)
@@ -67,7 +67,7 @@ def test_block_lists_match_brute_force(lay, par, block):
 
 @pytest.mark.parametrize("lay", LAYOUTS)
 @pytest.mark.parametrize("par", PARAMS)
-@pytest.mark.parametrize("block", [64, 128, 256])
+@pytest.mark.parametrize("block", [64, 128, 256, 384])
 def test_position_major_temporal_lists(lay, par, block):
     """The list a Temporal head walks over the position-major copy: the oracle's mask, rows and
     columns permuted into that order, scanned by brute force."""
@@ -94,7 +94,7 @@ def test_position_major_temporal_lists(lay, par, block):
 
 @pytest.mark.parametrize("lay", LAYOUTS)
 @pytest.mark.parametrize("tau", [1, 2, 3])
-@pytest.mark.parametrize("block", [64, 128, 256])
+@pytest.mark.parametrize("block", [64, 128, 256, 384])
 def test_textural_lists(lay, tau, block):
     """Video-only query blocks walk the compacted key sequence; blocks holding text rows walk token space."""
     L, P = orc.Layout(*lay), orc.Params(0.25, 0.25, tau)
@@ -108,7 +108,7 @@ def test_textural_lists(lay, tau, block):
     for qb in range(nb):
         ent = cols[row_ptr[qb]:row_ptr[qb + 1]]
         kbs, partial = ent & ~rf.RF_PLAN_PARTIAL, (ent & rf.RF_PLAN_PARTIAL) != 0
-        if (qb + 1) * block <= Nv and not (lay[3] > 0 and qb >= Nv // block):
+        if lay[3] == 0 or qb < Nv // block:  # no text rows in the block (a ragged last block of video rows included)
             nct = -(-Nc // TILE)
             assert kbs.tolist() == list(range(nct))
             assert partial.tolist() == [(kt + 1) * TILE > Nc for kt in range(nct)]
@@ -148,7 +148,7 @@ def test_text_first_lists_are_over_the_video_first_order(lay, block):
 
 
 @pytest.mark.parametrize("lay", LAYOUTS + [(33, 45, 80, 256), (13, 30, 45, 226)])
-@pytest.mark.parametrize("block", [64, 128, 256])
+@pytest.mark.parametrize("block", [64, 128, 256, 384])
 def test_query_block_order_is_a_permutation(lay, block):
     rl = rf.rf_layout(*lay)
     nqb = -(-(lay[0] * lay[1] * lay[2] + lay[3]) // block)
@@ -253,6 +253,8 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     assert attn(par=wide, D=128, block=256, ws=None) == -6  # accepted up to the workspace check
     assert attn(par=rf.rf_params(0.25, 0.25, 0, 0)) == -4 and attn(par=rf.rf_params(float("nan"), 0.25, 2, 0)) == -4
     assert attn(block=32) == -5 and attn(block=512) == -5 and attn(block=0) == -5
+    assert attn(block=384) == -5 and attn(block=384, D=128) == -5  # twelve-wavefront blocks: head_dim 96 only
+    assert attn(block=384, D=96, ws=None) == -6  # accepted up to the workspace check
     need = rf.rf_attention_workspace_bytes(1, 2, 64, L)
     # the work-queue counters, then a copy of K and of V: 2 heads x 256 tokens x 64 channels, bf16
     assert need == rf.RF_ATTENTION_MIN_WORKSPACE + 2 * 2 * 256 * 64 * 2
