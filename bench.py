@@ -55,7 +55,7 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="hunyuan720p")
-    ap.add_argument("--block", type=int, default=0, help="query rows per block (64|128|256, 384 at head_dim 96); 0 = the workload's")
+    ap.add_argument("--block", type=int, default=0, help="query rows per block (64|128|256|384); 0 = the workload's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wide-rows", action="store_true",
                     help="run the attention with RF_FLAG_WIDE_ROWS (64 query rows per wavefront; head_dim 128, block 256)")

@@ -91,7 +91,7 @@ enum rf_status {
     RF_ERR_LAYOUT = -3,    /* T, H, W < 1 or text_len < 0 */
     RF_ERR_PARAM = -4,     /* bandwidth outside [0, 1], tex_stride < 1, sample_interval < 0, unknown flags, bad sample_mode,
                               threshold not in [0, 1] or NaN */
-    RF_ERR_BLOCK = -5,     /* block not 64, 128 or 256 (or 384 at head_dim 96) */
+    RF_ERR_BLOCK = -5,     /* block not 64, 128, 256 or 384 */
     RF_ERR_WORKSPACE = -6, /* a required workspace is NULL, or a workspace is too small or misaligned */
     RF_ERR_HIP = -7,       /* a HIP runtime call failed (allocation, copy or launch) */
     RF_ERR_ALIGN = -8      /* a tensor is not 16-byte aligned, or the attention workspace not 256-byte aligned */
@@ -158,7 +158,7 @@ int rf_arm_classify_plus(const void *Q, const void *K, int B, int nH, int D, con
 /*
  * Sparse attention forward, Eq. 1-2 with the mask of each head's pattern (Eq. 3-5):
  *   O[b,h,i,:] = sum_j softmax_j(q_i . k_j / sqrt(D) over kept j) * v_j.
- * The mask is token-level; `block` (64, 128 or 256; also 384 at head_dim 96) is the number of query rows per block (= per
+ * The mask is token-level; `block` (64, 128, 256 or 384) is the number of query rows per block (= per
  * workgroup: larger blocks share each K/V tile among more queries and run faster on long sequences), and
  * (query block, 64-key tile) pairs with no kept token pair are skipped, so O does not
  * depend on it.  Scores and sums are accumulated in fp32, O is rounded to bf16.

@@ -131,7 +131,7 @@ int get_attention_plan(const Geometry& geometry, int block, DevicePlan* out) {
 
 int global_sample_count(const Geometry& g) { return (g.Nv + g.omega - 1) / g.omega; }
 
-bool valid_block(int block) { return block == 64 || block == 128 || block == 256 || block == 384; }  // query rows per block (384: head_dim 96 only)
+bool valid_block(int block) { return block == 64 || block == 128 || block == 256 || block == 384; }  // query rows per block
 
 // (token counts that overflow int32 indices were already refused by resolve_geometry)
 int check_shape(int B, int nH, int D) {
@@ -162,7 +162,7 @@ const char* rf_status_string(int status) {
         case RF_ERR_SHAPE: return "bad tensor shape";
         case RF_ERR_LAYOUT: return "bad video layout";
         case RF_ERR_PARAM: return "bad parameter";
-        case RF_ERR_BLOCK: return "block must be 64, 128 or 256 (or 384 at head_dim 96)";
+        case RF_ERR_BLOCK: return "block must be 64, 128, 256 or 384";
         case RF_ERR_WORKSPACE: return "workspace missing or too small";
         case RF_ERR_HIP: return "HIP runtime error";
         case RF_ERR_ALIGN: return "tensor or workspace pointer misaligned";
@@ -308,7 +308,7 @@ static int sparse_attention_impl(const void* Q, const void* K, const void* V, co
     if (st != RF_OK) return st;
     st = check_shape(B, nH, D);
     if (st != RF_OK) return st;
-    if (!valid_block(block) || (block == 384 && D != 96)) return RF_ERR_BLOCK;
+    if (!valid_block(block)) return RF_ERR_BLOCK;
     if (params && (params->flags & RF_FLAG_WIDE_ROWS) && (block != 256 || D != 128)) return RF_ERR_PARAM;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return RF_ERR_ALIGN;
     // the work-queue counters live in the first RF_ATTENTION_MIN_WORKSPACE bytes; a workspace of the

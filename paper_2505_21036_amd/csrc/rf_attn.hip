@@ -93,8 +93,9 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
     constexpr int DEPTH = SM::DEPTH;
     // how many slabs ahead of their MFMAs the LDS operand reads run: with two halves every slab feeds two
     // MFMAs and the registers are all in use, and two measured best (dense CogVideoX-shaped layer 4.25 ->
-    // 3.99 ms against the depths of the one-half loop)
-    constexpr int AK = QH == 2 ? 2 : kAheadK, AV = QH == 2 ? 2 : kAheadV;
+    // 3.99 ms against the depths of the one-half loop); twelve wavefronts at head_dim 128 have 168
+    // registers each, which the loops fit without spills at depth two
+    constexpr int AK = (QH == 2 || (NW == 12 && D == 128)) ? 2 : kAheadK, AV = (QH == 2 || (NW == 12 && D == 128)) ? 2 : kAheadV;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, m = lane & 31;
     const int N = pl.N, Nv = pl.Nv, keyN = qk.keyN, ntiles = qk.ntiles;
     // per-key side data staged through LDS two tiles ahead: the token index of each key of the
@@ -236,30 +237,32 @@ __device__ __forceinline__ void attend(const AttnArgs& a, const DevicePlan& pl, 
             const int* al = side + (t % SM::SIDE_SLOTS) * kTileK;
 #pragma unroll
             for (int h = 0; h < QH; ++h) {
-                if (MODE == MODE_LISTED && !(entry & kTileBoundary)) {
-                    // all 64 keys are video tokens: only the pattern's band decides
+                // this lane's keys come in runs of eight: keys 32*kb2 + 16*u + 8*hf .. +7 sit in registers 8*u .. 8*u+7
+                typedef __attribute__((address_space(3))) const u32x4 lds_u32x4;
+                const bool band_only = MODE == MODE_LISTED && !(entry & kTileBoundary);  // all 64 keys are video tokens
 #pragma unroll
-                    for (int kb2 = 0; kb2 < 2; ++kb2)
+                for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const uint32_t d = static_cast<uint32_t>(al[32 * kb2 + key_of_reg(r, hf)]) + q_lo[h];
-                            s[h][kb2][r] = d <= q_span[h] ? s[h][kb2][r] : -INFINITY;
-                        }
-                } else {
+                    for (int u = 0; u < 2; ++u) {
+                        const int base = 32 * kb2 + 16 * u + 8 * hf;
+                        uint32_t at[8] = {};
+                        if (MODE == MODE_LISTED) {
+                            const u32x4 a0 = *(lds_u32x4*)(uintptr_t)ST::lds_offset(reinterpret_cast<const unsigned char*>(al + base));
+                            const u32x4 a1 = *(lds_u32x4*)(uintptr_t)ST::lds_offset(reinterpret_cast<const unsigned char*>(al + base + 4));
 #pragma unroll
-                    for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int koff = 32 * kb2 + key_of_reg(r, hf);
-                            const int kidx = k0 + koff;
-                            bool ok = kidx < keyN;
-                            if (MODE == MODE_LISTED) {
-                                const uint32_t d = static_cast<uint32_t>(al[koff]) + q_lo[h];
-                                ok = ok & ((d <= q_span[h]) | (kidx >= Nv));
+                            for (int i = 0; i < 4; ++i) {
+                                at[i] = a0[i];
+                                at[4 + i] = a1[i];
                             }
-                            s[h][kb2][r] = ok ? s[h][kb2][r] : -INFINITY;
                         }
-                }
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            const int kidx = k0 + base + i;
+                            bool ok = band_only || kidx < keyN;
+                            if (MODE == MODE_LISTED) ok = ok & ((at[i] + q_lo[h] <= q_span[h]) | (!band_only && kidx >= Nv));
+                            s[h][kb2][8 * u + i] = ok ? s[h][kb2][8 * u + i] : -INFINITY;
+                        }
+                    }
             }
         }
     };
@@ -706,9 +709,11 @@ int launch_attention(const AttnArgs& a, int D, void* stream) {
     if (D == 64 && nw == 8) return launch_one<64, 4, LOOP_64>(a, st);
     if (D == 96 && nw == 8) return launch_one<96, 8>(a, st);
     if (D == 128 && nw == 8) return launch_one<128, 8>(a, st);
-    // 384-row blocks at head_dim 96: twelve wavefronts, three per SIMD at 168 registers (3-5 % faster
-    // than eight on 256 rows for every class; at head_dim 128 the listed loop does not fit 168 registers)
+    // 384-row blocks: twelve wavefronts, three per SIMD at 168 registers (3-7 % faster than eight on 256
+    // rows for every class at head_dim 96 and 128; even with the 64-row wavefronts at head_dim 64)
+    if (D == 64 && nw == 12) return launch_one<64, 12>(a, st);
     if (D == 96 && nw == 12) return launch_one<96, 12>(a, st);
+    if (D == 128 && nw == 12) return launch_one<128, 12>(a, st);
     return static_cast<int>(hipErrorInvalidValue);
 }
 

@@ -57,12 +57,12 @@ WORKLOADS = {
     # Open-Sora-Plan-1.2 720p-shaped layer
     "osp720p": Workload("osp720p", 1, 24, 96, 24, 45, 80, 0, 384, 1003),
     # HunyuanVideo 720p-shaped layer, 256 text tokens (headline)
-    "hunyuan720p": Workload("hunyuan720p", 1, 24, 128, 33, 45, 80, 256, 256, 1004),
+    "hunyuan720p": Workload("hunyuan720p", 1, 24, 128, 33, 45, 80, 256, 384, 1004),
     # planted-structure ARM validation
     "planted": Workload("planted", 2, 16, 128, 16, 32, 32, 0, 128, 1005,
                         planted=(SPATIAL, TEMPORAL, TEXTURAL)),
     # the headline shape with planted heads, so that the ARM picks all three patterns there
-    "hunyuan720p_planted": Workload("hunyuan720p_planted", 1, 24, 128, 33, 45, 80, 256, 256, 1009,
+    "hunyuan720p_planted": Workload("hunyuan720p_planted", 1, 24, 128, 33, 45, 80, 256, 384, 1009,
                                     planted=(SPATIAL, TEMPORAL, TEXTURAL)),
     # small ragged shapes for parity sweeps: frames not block aligned, ragged tail, text
     "ragged64": Workload("ragged64", 1, 3, 64, 5, 6, 11, 19, 64, 1006),

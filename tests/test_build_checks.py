@@ -61,3 +61,19 @@ def test_tile_loops_keep_operand_reads_ahead_of_the_mfmas():
         ahead = sum("lgkmcnt(3)" in x or "lgkmcnt(4)" in x for x in waits)
         assert ahead >= 24, (ahead, len(waits))
         assert not any(x.startswith("scratch_") for x in body)  # no spills inside a tile loop
+
+
+def test_twelve_wavefront_kernel_fits_its_registers():
+    """The kernel of the headline configuration (head_dim 128, 384-row blocks, twelve wavefronts) is
+    held to 168 registers so that three wavefronts share a SIMD.  A reload from scratch waits for every
+    vector-memory operation in flight, the tile loads included, so the loops that run on every tile
+    must hold none; the listed loop may reload lane offsets on its rare path (tiles that are not 64
+    consecutive rows), at most two."""
+    asm = device_assembly("rf_attn.hip")
+    loops = _tile_loops(asm, "_ZN2rf11attn_kernelILi128ELi12ELi0EEEvNS_8AttnArgsE")
+    assert len(loops) >= 4
+    spills = sorted(sum(x.startswith("scratch_") for x in body) for body in loops)
+    assert spills[:-1] == [0] * (len(loops) - 1) and spills[-1] <= 2, spills
+    m = re.search(r"\.amdhsa_kernel _ZN2rf11attn_kernelILi128ELi12ELi0EEEvNS_8AttnArgsE.*?\.amdhsa_next_free_vgpr\s+(\d+)", asm, re.S)
+    assert m and int(m.group(1)) <= 168
+

@@ -68,8 +68,6 @@ SMALL = ["tiny", "ragged64", "ragged96", "ragged128"]
 @pytest.mark.parametrize("scale", [1.0, 12.0])
 def test_small_shapes_every_class_every_row(name, block, scale):
     w = inp.WORKLOADS[name]
-    if block == 384 and w.D != 96:
-        pytest.skip("384-row blocks exist at head_dim 96 only")
     print("case", name, block, scale, flush=True)
     rp, op = par()
     _, ol = lay(w)
@@ -150,8 +148,6 @@ def test_text_first_every_class_every_row(name, block):
     """The same heads with their text rows moved to the front and RF_FLAG_TEXT_FIRST set, against
     the oracle's text-first reading; attention for every class, packed or not, and the ARM."""
     w = inp.WORKLOADS[name]
-    if block == 384 and w.D != 96:
-        pytest.skip("384-row blocks exist at head_dim 96 only")
     print("case text-first", name, block, flush=True)
     tl, scale = w.text_len, 6.0
     rl, ol = lay(w)
@@ -409,6 +405,8 @@ def test_hunyuan720p_headline_layer():
     sampled_parity(w, O, classes, [(0, 9), (0, 15), (0, 17)], 20, tag="thirds, packed")
     O = run_attention(w, Q, K, V, classes, 128, packed=True)
     sampled_parity(w, O, classes, [(0, 1), (0, 10), (0, 20)], 20, tag="thirds, packed, block 128")
+    O = run_attention(w, Q, K, V, classes, 256, packed=True)
+    sampled_parity(w, O, classes, [(0, 2), (0, 11), (0, 21)], 12, tag="thirds, packed, block 256")
     O = run_attention(w, Q, K, V, hc.flatten().tolist(), w.block, packed=True)  # as bench.py runs it
     sampled_parity(w, O, hc.flatten().tolist(), [(0, 5)], 12, tag="arm-chosen, packed")
     O = run_attention(w, Q, K, V, hc.flatten().tolist(), w.block)
@@ -540,7 +538,7 @@ def test_many_calls_on_three_streams_and_a_replayed_graph():
     # two full workspaces (packed copies), one with the counters only, one full for the graph
     wss = [torch.empty(n, dtype=torch.uint8, device=DEV) for n in (full, rf.RF_ATTENTION_MIN_WORKSPACE, full, full)]
     outs = [torch.empty_like(Q) for _ in range(4)]
-    blocks = (64, 128, 256, 128)
+    blocks = (64, 384, 256, 128)
     for i in range(4):  # lists built, kernel attributes set
         rf.rf_sparse_attention(Q, K, V, classes[i], rl, None, blocks[i], out=outs[i], workspace=wss[i])
     torch.cuda.synchronize()
@@ -594,7 +592,7 @@ def test_random_small_configurations():
         B, nH = int(rng.integers(1, 3)), int(rng.integers(1, 6))
         bs, bt = float(rng.choice([0.0, 0.07, 0.25, 0.5, 1.0])), float(rng.choice([0.0, 0.03, 0.25, 0.6, 1.0]))
         tau = int(rng.integers(1, 6))
-        block = int(rng.choice([64, 128, 256] + ([384, 384] if D == 96 else [])))
+        block = int(rng.choice([64, 128, 256, 384]))
         packed, text_first = bool(rng.integers(0, 2)), bool(rng.integers(0, 2)) and tl > 0
         scale = float(rng.choice([1.0, 4.0, 10.0]))
         w = inp.Workload("rand%d" % case, B, nH, D, T, H, W, tl, block, 5000 + case)

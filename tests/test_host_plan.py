@@ -253,8 +253,7 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     assert attn(par=wide, D=128, block=256, ws=None) == -6  # accepted up to the workspace check
     assert attn(par=rf.rf_params(0.25, 0.25, 0, 0)) == -4 and attn(par=rf.rf_params(float("nan"), 0.25, 2, 0)) == -4
     assert attn(block=32) == -5 and attn(block=512) == -5 and attn(block=0) == -5
-    assert attn(block=384) == -5 and attn(block=384, D=128) == -5  # twelve-wavefront blocks: head_dim 96 only
-    assert attn(block=384, D=96, ws=None) == -6  # accepted up to the workspace check
+    assert attn(block=384, ws=None) == -6 and attn(block=320) == -5  # 384 accepted up to the workspace check
     need = rf.rf_attention_workspace_bytes(1, 2, 64, L)
     # the work-queue counters, then a copy of K and of V: 2 heads x 256 tokens x 64 channels, bf16
     assert need == rf.RF_ATTENTION_MIN_WORKSPACE + 2 * 2 * 256 * 64 * 2
