@@ -26,7 +26,8 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 # profiles/attn_kernel_hunyuan720p.md (counter values in KiB, FETCH_SIZE scaled x2.0 and WRITE_SIZE
 # x1.0, what the same counters read for a 1 GiB device copy).  Only known for the workload / block
 # it was profiled on; the bench line says where the figure comes from.
-PROFILED_TRAFFIC_BYTES = {("hunyuan720p", 256): (2.0 * 9.5379e6 + 1.0 * 7.5577e5) * 1024}
+PROFILED_TRAFFIC_BYTES = {("hunyuan720p", 384): (2.0 * 7.9694e6 + 1.0 * 8.3882e5) * 1024,
+                          ("hunyuan720p", 256): (2.0 * 9.5379e6 + 1.0 * 7.5577e5) * 1024}
 
 
 def kept_pairs(cls, w, bw_s=0.25, bw_t=0.25, tau=2):
