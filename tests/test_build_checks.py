@@ -49,7 +49,7 @@ def _tile_loops(asm, kernel):
 
 
 def test_tile_loops_keep_operand_reads_ahead_of_the_mfmas():
-    """Performance guard on the generated code of the headline kernel (head_dim 128, 256-row blocks):
+    """Performance guard on the generated code of the eight-wavefront kernel (head_dim 128, 256-row blocks):
     in every tile loop the LDS operand reads run ahead of the MFMAs that use them, which shows as
     waits for all-but-3 / all-but-4 outstanding LDS operations.  (A schedule that reads, waits for
     everything and then issues one MFMA costs ~9 % and has appeared from unrelated edits.)"""
